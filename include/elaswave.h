@@ -1,0 +1,169 @@
+/*
+ * elaswave.h -- C ABI of the MI355X (gfx950) reshard + snapshot/checksum library.
+ *
+ * The library implements the data-parallel hot path of ElasWave's parameter
+ * recovery (arXiv 2510.00606): re-partitioning one DP group's flat ZeRO state
+ * from an old DP degree to a new one under the interleaved ZeRO assignment
+ * (Sec. 6.3), driven by the Live Remap transfer plan (Sec. 5.2), plus the
+ * per-step in-memory snapshot (Sec. 5.1) with per-block checksums for the
+ * "online verification" the abstract names.
+ *
+ * Conventions
+ *   - "host" pointers are ordinary process memory, "device" pointers are HIP
+ *     device memory of the current device.  Pointer ARRAYS (old_shards,
+ *     snapshots, new_shards) are host arrays whose entries are device pointers.
+ *   - All offsets and lengths in plans are in ELEMENTS, so one plan serves the
+ *     bf16 parameter array and the fp32 master / Adam m / Adam v arrays.
+ *   - Ranks: "old rank" indexes the DP group before the event (0..old_dp-1),
+ *     "new rank" after it (0..new_dp-1).  Survivors keep their relative order
+ *     and are renumbered densely from 0; joiners follow; if new_dp is smaller
+ *     than the number of survivors the highest survivors only give data away.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Kernel-launching calls enqueue work and return; the caller synchronises.
+ *   - Every call returns EW_OK (0) or a negative error code.  Nothing throws,
+ *     aborts or falls back to the CPU.  On error output arguments are untouched.
+ *   - The caller owns every device buffer it passes.  The library owns only the
+ *     plan object (host) and, after ew_plan_upload, its device tables.
+ */
+#ifndef ELASWAVE_H
+#define ELASWAVE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define EW_MAX_DP 64u            /* alive_mask is 64 bits wide                              */
+#define EW_GRANULE 8u            /* elements; piece boundaries inside a unit are multiples  */
+#define EW_CKSUM_BLOCK (1u << 20) /* bytes covered by one checksum record                   */
+
+enum {
+  EW_OK = 0,
+  EW_EINVAL = -1,          /* bad argument (zero degree, degree > 64, chunk 0, mask bits above
+                              old_dp, non-monotone unit boundaries, elem_size not 2 or 4, NULL
+                              where data is needed, plan not uploaded)                          */
+  EW_EUNRECOVERABLE = -2,  /* no survivor, or a failed rank whose ring predecessor failed too */
+  EW_ENOMEM = -3,          /* host or device allocation failed                                 */
+  EW_EHIP = -4             /* HIP runtime error; text of the last one via ew_strerror(EW_EHIP) */
+};
+
+typedef struct ew_plan ew_plan_t; /* opaque */
+
+/* One checksum record: wrapping sum and XOR of a block's little-endian u64 words. */
+typedef struct {
+  uint64_t sum;
+  uint64_t xr;
+} ew_cksum_t;
+
+#define EW_SEG_SNAPSHOT 1u /* source is the snapshot of src_owner's shard (src_owner failed)   */
+#define EW_SEG_LOCAL 2u    /* holder's new rank == dst_rank: bypasses the staging arena        */
+#define EW_NO_STAGE (~(uint64_t)0)
+
+/* One entry of the transfer plan: an element-exact cell fragment of the overlap
+ * matrix M_overlap (Sec. 5.2 step 2, Fig. 7b). 40 bytes. */
+typedef struct {
+  uint64_t src_off;   /* offset inside src_owner's OLD shard (live or snapshot copy)           */
+  uint64_t dst_off;   /* offset inside dst_rank's NEW shard                                    */
+  uint64_t stage_off; /* offset inside the staging arena; EW_NO_STAGE for LOCAL segments       */
+  uint64_t len;       /* elements, > 0                                                         */
+  uint16_t src_owner; /* old rank whose partition the data belongs to                          */
+  uint16_t holder;    /* old rank that serves it: src_owner if alive, else (src_owner-1) mod old_dp
+                         (worker i keeps the snapshot of worker (i+1) mod n, Sec. 5.1)          */
+  uint16_t dst_rank;  /* new rank                                                              */
+  uint16_t flags;     /* EW_SEG_*                                                              */
+} ew_seg_t;
+
+/* ---- Live Remap steps 1+2: integrity check and transfer plan (Sec. 5.2) -------------------
+ * Layout (Sec. 6.3, Fig. 10b): the flat state of `numel` elements is cut into units (the
+ * paper's layers) of `chunk` elements, the last one short; every unit of L elements is split
+ * uniformly over D ranks at b_j = min(L, 8*floor(j*ceil(L/8)/D)); rank j's shard is its piece
+ * of every unit, in unit order.  The plan intersects, unit by unit, what each surviving
+ * holder has (its own piece, plus its ring successor's piece from the snapshot if that
+ * successor failed) with the new layout's pieces.
+ * alive_mask: bit j set = old rank j survived.  *out receives a new plan (host memory) to be
+ * released with ew_plan_free.  Synchronous, no GPU work. */
+int ew_plan(uint32_t old_dp, uint32_t new_dp, uint64_t alive_mask, uint64_t numel, uint64_t chunk,
+            ew_plan_t **out);
+
+/* Same, with explicit unit boundaries (host array of n_units+1 ascending values,
+ * unit_starts[0] = 0, unit_starts[n_units] = numel; empty units allowed). */
+int ew_plan_bounds(uint32_t old_dp, uint32_t new_dp, uint64_t alive_mask, uint64_t n_units,
+                   const uint64_t *unit_starts, ew_plan_t **out);
+
+/* Frees host and device tables.  Work enqueued with this plan must have completed. */
+void ew_plan_free(ew_plan_t *plan);
+
+/* Plan queries (host, constant time).  Segments are ordered by unit, then by element. */
+uint64_t ew_plan_numel(const ew_plan_t *plan);
+uint32_t ew_plan_old_dp(const ew_plan_t *plan);
+uint32_t ew_plan_new_dp(const ew_plan_t *plan);
+uint64_t ew_plan_num_segs(const ew_plan_t *plan);
+const ew_seg_t *ew_plan_segs(const ew_plan_t *plan); /* borrowed; valid until ew_plan_free  */
+uint64_t ew_plan_old_shard_len(const ew_plan_t *plan, uint32_t old_rank); /* elements         */
+uint64_t ew_plan_new_shard_len(const ew_plan_t *plan, uint32_t new_rank); /* elements         */
+int32_t ew_plan_new_rank_of(const ew_plan_t *plan, uint32_t old_rank); /* -1: failed/leaving */
+int32_t ew_plan_holder_of(const ew_plan_t *plan, uint32_t old_rank);   /* rank serving its data */
+uint64_t ew_plan_stage_len(const ew_plan_t *plan);                     /* arena size, elements */
+/* Message of pair (holder -> new rank) inside the arena; messages are contiguous and laid
+ * out sorted by (dst_rank, holder).  Length 0 for pairs that exchange nothing. */
+uint64_t ew_plan_pair_len(const ew_plan_t *plan, uint32_t holder, uint32_t dst_rank);
+uint64_t ew_plan_pair_off(const ew_plan_t *plan, uint32_t holder, uint32_t dst_rank);
+uint64_t ew_plan_remote_elems(const ew_plan_t *plan); /* == stage_len                        */
+uint64_t ew_plan_num_tiles(const ew_plan_t *plan, int which /*0 pack, 1 unpack*/);
+
+/* Builds the copy-tile tables (segments cut into pieces of at most tile_elems elements;
+ * 0 = library default) and uploads them to the current device on `stream`.  Must precede
+ * ew_pack / ew_unpack.  Calling it again replaces the tables (previous work must be done). */
+int ew_plan_upload(ew_plan_t *plan, uint32_t tile_elems, void *stream);
+
+/* ---- Live Remap step 3, send side: gather into per-destination messages -------------------
+ * For every non-LOCAL segment copies len elements from the holder's live shard
+ * (old_shards[holder]) or from the snapshot of the failed owner (snapshots[src_owner]) to
+ * stage[stage_off ...].  old_shards / snapshots: host arrays of old_dp device pointers;
+ * entries the plan never reads may be NULL (failed ranks' live shards are never read).
+ * stage: device, ew_plan_stage_len()*elem_size bytes.  elem_size: 2 (bf16) or 4 (fp32).
+ * All buffers should be 16-byte aligned for full speed; any alignment is handled correctly. */
+int ew_pack(const ew_plan_t *plan, const void *const *old_shards, const void *const *snapshots,
+            void *stage, uint32_t elem_size, void *stream);
+
+/* ---- Live Remap step 3 receive side + step 4: build the new shards ------------------------
+ * Non-LOCAL segments: stage -> new_shards[dst_rank][dst_off...].  LOCAL segments (diagonal of
+ * M_overlap): old shard or locally held snapshot -> new shard directly.  Every element of
+ * every new shard is written exactly once.  new_shards: host array of new_dp device pointers,
+ * each ew_plan_new_shard_len()*elem_size bytes. */
+int ew_unpack(const ew_plan_t *plan, const void *stage, const void *const *old_shards,
+              const void *const *snapshots, void *const *new_shards, uint32_t elem_size,
+              void *stream);
+
+/* ---- Per-step snapshot (Sec. 5.1) with block checksums ------------------------------------
+ * dst[0..nbytes) = src[0..nbytes); cksums[b] = (wrapping u64 sum, XOR) of the little-endian
+ * 64-bit words of bytes [b*2^20, min((b+1)*2^20, nbytes)), a trailing partial word being
+ * zero-padded.  src, dst, cksums: device; cksums has ceil(nbytes / 2^20) records and is
+ * overwritten.  src and dst must not overlap.  nbytes = 0 is a no-op. */
+int ew_snapshot(const void *src, void *dst, uint64_t nbytes, ew_cksum_t *cksums, void *stream);
+
+/* ---- Integrity check of stored bytes (Live Remap step 1) ----------------------------------
+ * Recomputes the block checksums of buf into got[] (device, ceil(nbytes/2^20) records,
+ * overwritten) and compares them with expect[] (device).  *n_bad (device) receives the number
+ * of differing blocks; the first min(*n_bad, cap) of them are listed in ascending order in
+ * bad_blocks[] (device) with diffs[i] = (got.sum - expect.sum mod 2^64, got.xr ^ expect.xr)
+ * (device, cap records).  bad_blocks/diffs may be NULL when cap = 0. */
+int ew_verify(const void *buf, uint64_t nbytes, const ew_cksum_t *expect, ew_cksum_t *got,
+              uint64_t *n_bad, uint64_t *bad_blocks, ew_cksum_t *diffs, uint64_t cap,
+              void *stream);
+
+/* Launch-shape knobs for benchmarking sweeps (process-wide, not thread-safe; defaults are the
+ * tuned ones).  Names: "copy_wgs_per_cu", "cksum_sub_bytes", "cksum_wgs_per_cu".
+ * Returns EW_EINVAL for an unknown name or an out-of-range value. */
+int ew_set_param(const char *name, int64_t value);
+int64_t ew_get_param(const char *name);
+
+const char *ew_strerror(int code);
+const char *ew_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ELASWAVE_H */
