@@ -49,7 +49,7 @@ enum {
   EW_EHIP = -4             /* HIP runtime error; text of the last one via ew_strerror(EW_EHIP) */
 };
 
-typedef struct ew_plan ew_plan_t; /* opaque */
+typedef struct ew_plan_s ew_plan_t; /* opaque */
 
 /* One checksum record: wrapping sum and XOR of a block's little-endian u64 words. */
 typedef struct {
@@ -155,7 +155,7 @@ int ew_verify(const void *buf, uint64_t nbytes, const ew_cksum_t *expect, ew_cks
               void *stream);
 
 /* Launch-shape knobs for benchmarking sweeps (process-wide, not thread-safe; defaults are the
- * tuned ones).  Names: "copy_wgs_per_cu", "cksum_sub_bytes", "cksum_wgs_per_cu".
+ * tuned ones).  Names: "tile_elems", "copy_wgs_per_cu", "cksum_sub_bytes", "cksum_wgs_per_cu".
  * Returns EW_EINVAL for an unknown name or an out-of-range value. */
 int ew_set_param(const char *name, int64_t value);
 int64_t ew_get_param(const char *name);

@@ -1,0 +1,13 @@
+"""MI355X-native reshard + snapshot/checksum path of ElasWave (arXiv 2510.00606).
+
+  binding   ctypes wrappers with the names of include/elaswave.h (the product path)
+  build     compiles csrc/ into libelaswave.so for gfx950
+  synth     seeded synthetic inputs (no arithmetic of the method)
+  configs   the benchmark/test workloads (shapes, DP changes, unit boundaries)
+"""
+from .binding import (  # noqa: F401
+    EW_CKSUM_BLOCK, EW_EHIP, EW_EINVAL, EW_ENOMEM, EW_EUNRECOVERABLE, EW_GRANULE, EW_MAX_DP, EW_NO_STAGE, EW_OK,
+    EW_SEG_LOCAL, EW_SEG_SNAPSHOT, CKSUM_DTYPE, SEG_DTYPE, EwError, Plan, ew_get_param, ew_pack, ew_plan,
+    ew_plan_bounds, ew_plan_upload, ew_set_param, ew_snapshot, ew_strerror, ew_unpack, ew_verify, ew_version,
+    num_blocks,
+)

@@ -1,0 +1,510 @@
+// HIP kernels for gfx950 (MI355X, wave64) and their launch code:
+//   ew_segcopy_kernel   tile-table-driven copy: pack (Live Remap step 3, send side) and
+//                       unpack (receive side + step 4), Sec. 5.2
+//   ew_cksum_kernel     per-step snapshot copy fused with the per-block checksum (Sec. 5.1 and
+//                       the "online verification" of the abstract); read-only form for verify
+//   ew_compare_kernel   ordered list of blocks whose checksum changed
+// All of them are HBM-bandwidth bound (no contraction anywhere, hence no MFMA): the work is
+// 128-bit loads/stores, several in flight per lane, with a 64-bit integer fold on the side.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "plan_internal.h"
+
+namespace {
+
+using ew::Tile;
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 256;  // 4 waves of 64
+constexpr int kUnroll = 4;     // 16-byte loads in flight per lane in the unrolled body
+
+thread_local std::string g_hip_error = "no HIP error recorded";
+
+int hip_fail(hipError_t e, const char *what) {
+  g_hip_error = std::string(what) + ": " + hipGetErrorString(e);
+  return EW_EHIP;
+}
+#define EW_HIP(call)                                  \
+  do {                                                \
+    hipError_t e__ = (call);                          \
+    if (e__ != hipSuccess) return hip_fail(e__, #call); \
+  } while (0)
+
+// process-wide launch-shape knobs (see ew_set_param)
+int64_t g_copy_wgs_per_cu = 8;     // persistent grid = CUs * this; 0 = one workgroup per tile
+int64_t g_cksum_sub_bytes = 65536; // bytes of a checksum block handled by one workgroup pass
+int64_t g_cksum_wgs_per_cu = 0;    // 0 = one workgroup per sub-block, else persistent grid
+int64_t g_default_tile_elems = 8192;
+
+int num_cus() {
+  static int cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cached[dev] == 0) {
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return 256;
+    cached[dev] = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  }
+  return cached[dev];
+}
+
+__device__ __forceinline__ u32x4 load16(const u32x4 *p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ void store16(u32x4 *p, u32x4 v) { __builtin_nontemporal_store(v, p); }
+
+// ------------------------------------------------------------------------------------------
+// Segment copy.  One workgroup handles one tile at a time; tiles never straddle a segment, so
+// a tile is a plain contiguous copy between two buffers picked from the pointer tables.
+// ------------------------------------------------------------------------------------------
+struct CopyTabs {
+  const char *src[ew::kNumSrc];
+  char *dst[ew::kNumDst];
+};
+
+template <int ES>
+__global__ __launch_bounds__(kThreads) void ew_segcopy_kernel(const Tile *__restrict__ tiles,
+                                                              uint64_t ntiles, CopyTabs tabs) {
+  for (uint64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+    const Tile tl = tiles[t];
+    const char *s = tabs.src[tl.src_buf] + tl.src_off * ES;
+    char *d = tabs.dst[tl.dst_buf] + tl.dst_off * ES;
+    const uint32_t nbytes = tl.len * ES;
+    if ((((uintptr_t)s | (uintptr_t)d) & 15u) == 0) {
+      const u32x4 *sv = reinterpret_cast<const u32x4 *>(s);
+      u32x4 *dv = reinterpret_cast<u32x4 *>(d);
+      const uint32_t nvec = nbytes >> 4;
+      uint32_t i = threadIdx.x;
+      for (; i + (kUnroll - 1) * kThreads < nvec; i += kUnroll * kThreads) {
+        u32x4 r[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) r[u] = load16(sv + i + u * kThreads);
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) store16(dv + i + u * kThreads, r[u]);
+      }
+      for (; i < nvec; i += kThreads) store16(dv + i, load16(sv + i));
+      // fewer than 16 trailing bytes: whole elements, one per lane
+      const uint32_t done = nvec << 4;
+      const uint32_t rem = (nbytes - done) / ES;
+      if (threadIdx.x < rem) {
+        if (ES == 2)
+          reinterpret_cast<uint16_t *>(d + done)[threadIdx.x] =
+              reinterpret_cast<const uint16_t *>(s + done)[threadIdx.x];
+        else
+          reinterpret_cast<uint32_t *>(d + done)[threadIdx.x] =
+              reinterpret_cast<const uint32_t *>(s + done)[threadIdx.x];
+      }
+    } else {
+      // a unit whose length is not a multiple of 8 elements shifts later pieces off the
+      // 16-byte grid: element-wise copy (buffers are always element-aligned)
+      if (ES == 2) {
+        const uint16_t *se = reinterpret_cast<const uint16_t *>(s);
+        uint16_t *de = reinterpret_cast<uint16_t *>(d);
+        for (uint32_t i = threadIdx.x; i < tl.len; i += kThreads) de[i] = se[i];
+      } else {
+        const uint32_t *se = reinterpret_cast<const uint32_t *>(s);
+        uint32_t *de = reinterpret_cast<uint32_t *>(d);
+        for (uint32_t i = threadIdx.x; i < tl.len; i += kThreads) de[i] = se[i];
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Snapshot + checksum.  A checksum block (1 MiB) is cut into sub-blocks of `sub` bytes
+// (a power of two, 4 KiB..1 MiB); a workgroup streams one sub-block, folding the 64-bit
+// words into (sum, xor) per lane, then across the wave with shuffles, then across the four
+// waves through LDS.  With sub < 1 MiB the partial results of a block meet in its record
+// through 64-bit atomics; sum and xor are commutative, so the bits do not depend on order.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ void fold(u32x4 v, uint64_t &sum, uint64_t &xr) {
+  const uint64_t w0 = (uint64_t)v.x | ((uint64_t)v.y << 32);
+  const uint64_t w1 = (uint64_t)v.z | ((uint64_t)v.w << 32);
+  sum += w0 + w1;
+  xr ^= w0 ^ w1;
+}
+
+__device__ __forceinline__ uint64_t shfl_xor64(uint64_t v, int mask) {
+  const uint32_t lo = __shfl_xor((int)(uint32_t)v, mask, 64);
+  const uint32_t hi = __shfl_xor((int)(uint32_t)(v >> 32), mask, 64);
+  return (uint64_t)lo | ((uint64_t)hi << 32);
+}
+
+template <bool COPY, bool ALIGNED>
+__global__ __launch_bounds__(kThreads) void ew_cksum_kernel(const char *__restrict__ src,
+                                                            char *__restrict__ dst, uint64_t nbytes,
+                                                            ew_cksum_t *out, uint32_t sub,
+                                                            uint32_t accumulate) {
+  __shared__ uint64_t lds_sum[kThreads / 64];
+  __shared__ uint64_t lds_xor[kThreads / 64];
+  const uint64_t nsub = (nbytes + sub - 1) / sub;
+  for (uint64_t c = blockIdx.x; c < nsub; c += gridDim.x) {
+    const uint64_t begin = c * sub;
+    const uint64_t left = nbytes - begin;
+    const uint32_t n = left < sub ? (uint32_t)left : sub;
+    uint64_t sum = 0, xr = 0;
+    if (ALIGNED) {
+      const u32x4 *sv = reinterpret_cast<const u32x4 *>(src + begin);
+      u32x4 *dv = reinterpret_cast<u32x4 *>(dst + begin);
+      const uint32_t nvec = n >> 4;
+      uint32_t i = threadIdx.x;
+      for (; i + (kUnroll - 1) * kThreads < nvec; i += kUnroll * kThreads) {
+        u32x4 r[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) r[u] = load16(sv + i + u * kThreads);
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+          if (COPY) store16(dv + i + u * kThreads, r[u]);
+          fold(r[u], sum, xr);
+        }
+      }
+      for (; i < nvec; i += kThreads) {
+        const u32x4 r = load16(sv + i);
+        if (COPY) store16(dv + i, r);
+        fold(r, sum, xr);
+      }
+      // fewer than 16 trailing bytes (only at the very end of the buffer): one lane copies
+      // them and folds them as up to two zero-padded little-endian words
+      const uint32_t done = nvec << 4;
+      if (threadIdx.x == 0 && done < n) {
+        uint64_t w[2] = {0, 0};
+        for (uint32_t b = done; b < n; ++b) {
+          const uint8_t v = (uint8_t)src[begin + b];
+          if (COPY) dst[begin + b] = (char)v;
+          w[(b - done) >> 3] |= (uint64_t)v << (8 * ((b - done) & 7));
+        }
+        sum += w[0] + w[1];
+        xr ^= w[0] ^ w[1];
+      }
+    } else {
+      // unaligned base: byte loads, one 64-bit word per lane per step
+      const uint32_t nwords = (n + 7) >> 3;
+      for (uint32_t wi = threadIdx.x; wi < nwords; wi += kThreads) {
+        uint64_t w = 0;
+        const uint32_t b0 = wi << 3;
+        const uint32_t nb = (n - b0) < 8 ? (n - b0) : 8;
+        for (uint32_t b = 0; b < nb; ++b) {
+          const uint8_t v = (uint8_t)src[begin + b0 + b];
+          if (COPY) dst[begin + b0 + b] = (char)v;
+          w |= (uint64_t)v << (8 * b);
+        }
+        sum += w;
+        xr ^= w;
+      }
+    }
+    // wave fold
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) {
+      sum += shfl_xor64(sum, m);
+      xr ^= shfl_xor64(xr, m);
+    }
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) {
+      lds_sum[wave] = sum;
+      lds_xor[wave] = xr;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      uint64_t s = 0, x = 0;
+#pragma unroll
+      for (int w = 0; w < kThreads / 64; ++w) {
+        s += lds_sum[w];
+        x ^= lds_xor[w];
+      }
+      ew_cksum_t *rec = out + (begin >> 20);
+      if (accumulate) {
+        atomicAdd(reinterpret_cast<unsigned long long *>(&rec->sum), (unsigned long long)s);
+        atomicXor(reinterpret_cast<unsigned long long *>(&rec->xr), (unsigned long long)x);
+      } else {
+        rec->sum = s;
+        rec->xr = x;
+      }
+    }
+    __syncthreads();  // LDS is reused by the next sub-block of a persistent workgroup
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void ew_zero_kernel(uint64_t *p, uint64_t nwords) {
+  const uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i < nwords) p[i] = 0;
+}
+
+// Single workgroup: ascending list of differing blocks (stable compaction with ballots).
+constexpr int kCmpThreads = 1024;
+__global__ __launch_bounds__(kCmpThreads) void ew_compare_kernel(const ew_cksum_t *__restrict__ got,
+                                                                 const ew_cksum_t *__restrict__ expect,
+                                                                 uint64_t nblocks, uint64_t *n_bad,
+                                                                 uint64_t *bad_blocks, ew_cksum_t *diffs,
+                                                                 uint64_t cap) {
+  __shared__ uint32_t wave_cnt[kCmpThreads / 64];
+  __shared__ uint64_t base;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (threadIdx.x == 0) base = 0;
+  __syncthreads();
+  for (uint64_t b0 = 0; b0 < nblocks; b0 += kCmpThreads) {
+    const uint64_t b = b0 + threadIdx.x;
+    ew_cksum_t g = {0, 0}, e = {0, 0};
+    bool bad = false;
+    if (b < nblocks) {
+      g = got[b];
+      e = expect[b];
+      bad = (g.sum != e.sum) || (g.xr != e.xr);
+    }
+    const uint64_t ballot = __ballot(bad);
+    if (lane == 0) wave_cnt[wave] = (uint32_t)__popcll(ballot);
+    __syncthreads();
+    uint64_t before = base, total = 0;
+    for (int w = 0; w < kCmpThreads / 64; ++w) {
+      if (w < wave) before += wave_cnt[w];
+      total += wave_cnt[w];
+    }
+    if (bad) {
+      const uint64_t slot = before + (uint64_t)__popcll(ballot & ((1ull << lane) - 1ull));
+      if (slot < cap) {
+        bad_blocks[slot] = b;
+        diffs[slot].sum = g.sum - e.sum;
+        diffs[slot].xr = g.xr ^ e.xr;
+      }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) base += total;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *n_bad = base;
+}
+
+// ------------------------------------------------------------------------------------------
+// launch helpers
+// ------------------------------------------------------------------------------------------
+int upload_tiles(const ew_plan_t &plan, int which, uint32_t tile_elems, ew::DeviceTiles &dt,
+                 hipStream_t stream) {
+  std::vector<Tile> tiles;
+  try {
+    ew::build_tiles(plan, which, tile_elems, tiles);
+  } catch (const std::bad_alloc &) {
+    return EW_ENOMEM;
+  }
+  dt.count = tiles.size();
+  if (tiles.empty()) return EW_OK;
+  const size_t bytes = tiles.size() * sizeof(Tile);
+  if (hipHostMalloc((void **)&dt.host, bytes, hipHostMallocDefault) != hipSuccess) return EW_ENOMEM;
+  std::memcpy(dt.host, tiles.data(), bytes);
+  if (hipMalloc((void **)&dt.dev, bytes) != hipSuccess) return EW_ENOMEM;
+  EW_HIP(hipMemcpyAsync(dt.dev, dt.host, bytes, hipMemcpyHostToDevice, stream));
+  return EW_OK;
+}
+
+void release_tiles(ew::DeviceTiles &dt) {
+  if (dt.dev) (void)hipFree(dt.dev);
+  if (dt.host) (void)hipHostFree(dt.host);
+  dt = ew::DeviceTiles();
+}
+
+int launch_segcopy(const ew::DeviceTiles &dt, const CopyTabs &tabs, uint32_t elem_size,
+                   hipStream_t stream) {
+  if (dt.count == 0) return EW_OK;
+  uint64_t grid = dt.count;
+  if (g_copy_wgs_per_cu > 0) {
+    const uint64_t cap = (uint64_t)num_cus() * (uint64_t)g_copy_wgs_per_cu;
+    if (grid > cap) grid = cap;
+  }
+  if (grid > 0x7fffffffull) grid = 0x7fffffffull;
+  if (elem_size == 2)
+    hipLaunchKernelGGL(ew_segcopy_kernel<2>, dim3((uint32_t)grid), dim3(kThreads), 0, stream, dt.dev,
+                       dt.count, tabs);
+  else
+    hipLaunchKernelGGL(ew_segcopy_kernel<4>, dim3((uint32_t)grid), dim3(kThreads), 0, stream, dt.dev,
+                       dt.count, tabs);
+  EW_HIP(hipGetLastError());
+  return EW_OK;
+}
+
+int launch_zero(void *p, uint64_t nbytes, hipStream_t stream) {
+  const uint64_t nwords = nbytes / 8;
+  if (nwords == 0) return EW_OK;
+  const uint64_t grid = (nwords + kThreads - 1) / kThreads;
+  hipLaunchKernelGGL(ew_zero_kernel, dim3((uint32_t)grid), dim3(kThreads), 0, stream, (uint64_t *)p,
+                     nwords);
+  EW_HIP(hipGetLastError());
+  return EW_OK;
+}
+
+template <bool COPY>
+int launch_cksum(const void *src, void *dst, uint64_t nbytes, ew_cksum_t *out, hipStream_t stream) {
+  const uint32_t sub = (uint32_t)g_cksum_sub_bytes;
+  const uint64_t nblocks = (nbytes + EW_CKSUM_BLOCK - 1) / EW_CKSUM_BLOCK;
+  const uint32_t accumulate = sub < EW_CKSUM_BLOCK ? 1u : 0u;
+  if (accumulate) {
+    const int rc = launch_zero(out, nblocks * sizeof(ew_cksum_t), stream);
+    if (rc != EW_OK) return rc;
+  }
+  uint64_t grid = (nbytes + sub - 1) / sub;
+  if (g_cksum_wgs_per_cu > 0) {
+    const uint64_t cap = (uint64_t)num_cus() * (uint64_t)g_cksum_wgs_per_cu;
+    if (grid > cap) grid = cap;
+  }
+  if (grid > 0x7fffffffull) grid = 0x7fffffffull;
+  const bool aligned = ((((uintptr_t)src) | (COPY ? (uintptr_t)dst : 0)) & 15u) == 0;
+  if (aligned)
+    hipLaunchKernelGGL((ew_cksum_kernel<COPY, true>), dim3((uint32_t)grid), dim3(kThreads), 0, stream,
+                       (const char *)src, (char *)dst, nbytes, out, sub, accumulate);
+  else
+    hipLaunchKernelGGL((ew_cksum_kernel<COPY, false>), dim3((uint32_t)grid), dim3(kThreads), 0, stream,
+                       (const char *)src, (char *)dst, nbytes, out, sub, accumulate);
+  EW_HIP(hipGetLastError());
+  return EW_OK;
+}
+
+int fill_tabs(const ew_plan_t *plan, const void *const *old_shards, const void *const *snapshots,
+              CopyTabs &tabs, bool need_local_only) {
+  std::memset(&tabs, 0, sizeof(tabs));
+  (void)need_local_only;
+  for (uint32_t j = 0; j < plan->old_dp; ++j) {
+    const void *live = old_shards ? old_shards[j] : nullptr;
+    const void *snap = snapshots ? snapshots[j] : nullptr;
+    if (((plan->live_read >> j) & 1) && !live) return EW_EINVAL;
+    if (((plan->snap_read >> j) & 1) && !snap) return EW_EINVAL;
+    tabs.src[ew::kSrcLive + j] = (const char *)live;
+    tabs.src[ew::kSrcSnap + j] = (const char *)snap;
+  }
+  return EW_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+void ew_plan_free(ew_plan_t *plan) {
+  if (!plan) return;
+  release_tiles(plan->pack);
+  release_tiles(plan->unpack);
+  delete plan;
+}
+
+uint64_t ew_plan_num_tiles(const ew_plan_t *plan, int which) {
+  if (!plan || (which != 0 && which != 1)) return 0;
+  if (plan->tile_elems) return which == 0 ? plan->pack.count : plan->unpack.count;
+  return ew::count_tiles(*plan, which, (uint32_t)g_default_tile_elems);
+}
+
+int ew_plan_upload(ew_plan_t *plan, uint32_t tile_elems, void *stream) {
+  if (!plan) return EW_EINVAL;
+  if (tile_elems == 0) tile_elems = (uint32_t)g_default_tile_elems;
+  if (tile_elems > (1u << 24)) return EW_EINVAL;
+  release_tiles(plan->pack);
+  release_tiles(plan->unpack);
+  plan->tile_elems = 0;
+  int dev = 0;
+  EW_HIP(hipGetDevice(&dev));
+  int rc = upload_tiles(*plan, 0, tile_elems, plan->pack, (hipStream_t)stream);
+  if (rc == EW_OK) rc = upload_tiles(*plan, 1, tile_elems, plan->unpack, (hipStream_t)stream);
+  if (rc != EW_OK) {
+    release_tiles(plan->pack);
+    release_tiles(plan->unpack);
+    return rc;
+  }
+  plan->device = dev;
+  plan->tile_elems = tile_elems;
+  return EW_OK;
+}
+
+int ew_pack(const ew_plan_t *plan, const void *const *old_shards, const void *const *snapshots,
+            void *stage, uint32_t elem_size, void *stream) {
+  if (!plan || plan->tile_elems == 0 || (elem_size != 2 && elem_size != 4)) return EW_EINVAL;
+  if (plan->pack.count == 0) return EW_OK;
+  if (!stage) return EW_EINVAL;
+  CopyTabs tabs;
+  const int rc = fill_tabs(plan, old_shards, snapshots, tabs, false);
+  if (rc != EW_OK) return rc;
+  tabs.dst[ew::kDstStage] = (char *)stage;
+  return launch_segcopy(plan->pack, tabs, elem_size, (hipStream_t)stream);
+}
+
+int ew_unpack(const ew_plan_t *plan, const void *stage, const void *const *old_shards,
+              const void *const *snapshots, void *const *new_shards, uint32_t elem_size,
+              void *stream) {
+  if (!plan || plan->tile_elems == 0 || (elem_size != 2 && elem_size != 4)) return EW_EINVAL;
+  if (plan->unpack.count == 0) return EW_OK;
+  if (!new_shards) return EW_EINVAL;
+  if (plan->stage_len > 0 && !stage) return EW_EINVAL;
+  CopyTabs tabs;
+  const int rc = fill_tabs(plan, old_shards, snapshots, tabs, true);
+  if (rc != EW_OK) return rc;
+  tabs.src[ew::kSrcStage] = (const char *)stage;
+  for (uint32_t k = 0; k < plan->new_dp; ++k) {
+    if (plan->new_len[k] > 0 && !new_shards[k]) return EW_EINVAL;
+    tabs.dst[k] = (char *)new_shards[k];
+  }
+  return launch_segcopy(plan->unpack, tabs, elem_size, (hipStream_t)stream);
+}
+
+int ew_snapshot(const void *src, void *dst, uint64_t nbytes, ew_cksum_t *cksums, void *stream) {
+  if (nbytes == 0) return EW_OK;
+  if (!src || !dst || !cksums) return EW_EINVAL;
+  return launch_cksum<true>(src, dst, nbytes, cksums, (hipStream_t)stream);
+}
+
+int ew_verify(const void *buf, uint64_t nbytes, const ew_cksum_t *expect, ew_cksum_t *got,
+              uint64_t *n_bad, uint64_t *bad_blocks, ew_cksum_t *diffs, uint64_t cap, void *stream) {
+  if (!n_bad) return EW_EINVAL;
+  if (nbytes > 0 && (!buf || !expect || !got)) return EW_EINVAL;
+  if (cap > 0 && (!bad_blocks || !diffs)) return EW_EINVAL;
+  if (nbytes > 0) {
+    const int rc = launch_cksum<false>(buf, nullptr, nbytes, got, (hipStream_t)stream);
+    if (rc != EW_OK) return rc;
+  }
+  const uint64_t nblocks = (nbytes + EW_CKSUM_BLOCK - 1) / EW_CKSUM_BLOCK;
+  hipLaunchKernelGGL(ew_compare_kernel, dim3(1), dim3(kCmpThreads), 0, (hipStream_t)stream, got, expect,
+                     nblocks, n_bad, bad_blocks, diffs, cap);
+  EW_HIP(hipGetLastError());
+  return EW_OK;
+}
+
+int ew_set_param(const char *name, int64_t value) {
+  if (!name) return EW_EINVAL;
+  if (!std::strcmp(name, "copy_wgs_per_cu")) {
+    if (value < 0 || value > 64) return EW_EINVAL;
+    g_copy_wgs_per_cu = value;
+  } else if (!std::strcmp(name, "cksum_sub_bytes")) {
+    if (value < 4096 || value > (int64_t)EW_CKSUM_BLOCK || (value & (value - 1))) return EW_EINVAL;
+    g_cksum_sub_bytes = value;
+  } else if (!std::strcmp(name, "cksum_wgs_per_cu")) {
+    if (value < 0 || value > 64) return EW_EINVAL;
+    g_cksum_wgs_per_cu = value;
+  } else if (!std::strcmp(name, "tile_elems")) {
+    if (value < 64 || value > (1 << 24)) return EW_EINVAL;
+    g_default_tile_elems = value;
+  } else {
+    return EW_EINVAL;
+  }
+  return EW_OK;
+}
+
+int64_t ew_get_param(const char *name) {
+  if (!name) return -1;
+  if (!std::strcmp(name, "copy_wgs_per_cu")) return g_copy_wgs_per_cu;
+  if (!std::strcmp(name, "cksum_sub_bytes")) return g_cksum_sub_bytes;
+  if (!std::strcmp(name, "cksum_wgs_per_cu")) return g_cksum_wgs_per_cu;
+  if (!std::strcmp(name, "tile_elems")) return g_default_tile_elems;
+  return -1;
+}
+
+const char *ew_strerror(int code) {
+  switch (code) {
+    case EW_OK: return "ok";
+    case EW_EINVAL: return "invalid argument";
+    case EW_EUNRECOVERABLE:
+      return "unrecoverable: no survivor, or a failed rank's snapshot holder (ring predecessor) failed too";
+    case EW_ENOMEM: return "out of memory";
+    case EW_EHIP: return g_hip_error.c_str();
+    default: return "unknown error code";
+  }
+}
+
+const char *ew_version(void) { return "elaswave-mi355x 0.1 (gfx950)"; }
+
+}  // extern "C"

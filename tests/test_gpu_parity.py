@@ -1,0 +1,224 @@
+"""GPU parity tests: the HIP path (through the C ABI) against the CPU oracle, bit for bit.
+Small and ragged cases here; the five named workloads are in test_gpu_workloads.py."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2510_00606_amd as ew
+from oracle import checksum, layout
+
+from gpu_util import DEV, GUARD, guard_intact, guarded, np_bits, random_shards, run_reshard, stream, to_dev
+
+pytestmark = pytest.mark.gpu
+
+MIB = 1 << 20
+
+
+@pytest.fixture(autouse=True)
+def default_params():
+    saved = {k: ew.ew_get_param(k) for k in ("tile_elems", "copy_wgs_per_cu", "cksum_sub_bytes", "cksum_wgs_per_cu")}
+    yield
+    for k, v in saved.items():
+        ew.ew_set_param(k, v)
+
+
+# ------------------------------------------------------------------ snapshot + checksum
+def snapshot_case(nbytes, rng, src_shift=0, dst_shift=0):
+    raw = rng.integers(0, 256, nbytes + 64, dtype=np.uint8)
+    src_all = torch.from_numpy(raw).to(DEV)
+    src = src_all[src_shift:src_shift + nbytes]
+    dst_all = torch.full((nbytes + 128,), 0x5A, dtype=torch.uint8, device=DEV)
+    dst = dst_all[dst_shift:dst_shift + nbytes]
+    nb = ew.num_blocks(nbytes)
+    ck = torch.full((nb + 1, 2), -1, dtype=torch.int64, device=DEV)
+    ew.ew_snapshot(src, dst, nbytes, ck, stream())
+    torch.cuda.synchronize()
+    host = raw[src_shift:src_shift + nbytes]
+    assert np.array_equal(dst.cpu().numpy(), host), "snapshot bytes differ"
+    assert bool((dst_all[:dst_shift] == 0x5A).all()) and bool((dst_all[dst_shift + nbytes:] == 0x5A).all())
+    want = checksum.block_checksums(host)
+    got = ck.cpu().numpy().view(np.uint64)
+    assert np.array_equal(got[:nb], want), "checksums differ"
+    assert (got[nb] == np.uint64((1 << 64) - 1)).all(), "record past the end was written"
+
+
+SIZES = [0, 1, 7, 8, 9, 15, 16, 17, 255, 4096, 4096 * 3 + 5, 65536, 65536 + 16, 65536 * 5 - 3, MIB - 16, MIB - 1, MIB,
+         MIB + 1, MIB + 8, MIB + 4096, 3 * MIB + 12345, 17 * MIB + 65536 + 24]
+
+
+@pytest.mark.parametrize("nbytes", SIZES)
+def test_snapshot_matches_oracle(nbytes):
+    snapshot_case(nbytes, np.random.default_rng(nbytes))
+
+
+@pytest.mark.parametrize("sub,wgs", [(4096, 0), (16384, 2), (65536, 0), (262144, 1), (MIB, 0), (MIB, 3)])
+def test_snapshot_launch_shapes(sub, wgs):
+    ew.ew_set_param("cksum_sub_bytes", sub)
+    ew.ew_set_param("cksum_wgs_per_cu", wgs)
+    for nbytes in (1, 4097, MIB - 8, 9 * MIB + 100000 + 3, 64 * MIB):
+        snapshot_case(nbytes, np.random.default_rng(sub + wgs + nbytes))
+
+
+@pytest.mark.parametrize("shift", [(1, 0), (0, 3), (8, 8), (5, 11)])
+def test_snapshot_unaligned_buffers(shift):
+    for nbytes in (1, 100, 4096 + 7, 2 * MIB + 77):
+        snapshot_case(nbytes, np.random.default_rng(nbytes + shift[0]), *shift)
+
+
+def test_snapshot_closed_forms():
+    n = 131072  # words in one block
+    for words, want in ((np.zeros(n, np.uint64), (0, 0)),
+                        (np.full(n, (1 << 64) - 1, np.uint64), ((-n) % (1 << 64), 0)),
+                        (np.arange(n, dtype=np.uint64), (8589869056, 0))):
+        src = torch.from_numpy(words.view(np.int64)).to(DEV)
+        dst = torch.empty_like(src)
+        ck = torch.zeros((1, 2), dtype=torch.int64, device=DEV)
+        ew.ew_snapshot(src, dst, n * 8, ck, stream())
+        got = ck.cpu().numpy().view(np.uint64)[0]
+        assert (int(got[0]), int(got[1])) == want
+
+
+# ------------------------------------------------------------------ verify
+def verify_case(nbytes, flips, rng, cap=16):
+    raw = rng.integers(0, 256, nbytes, dtype=np.uint8)
+    buf = torch.from_numpy(raw).to(DEV)
+    nb = ew.num_blocks(nbytes)
+    snap = torch.empty_like(buf)
+    stored = torch.zeros((max(nb, 1), 2), dtype=torch.int64, device=DEV)
+    ew.ew_snapshot(buf, snap, nbytes, stored, stream())
+    torch.cuda.synchronize()
+    host = raw.copy()
+    for (o, bit) in flips:
+        host[o] ^= np.uint8(1 << bit)
+        snap[o] ^= (1 << bit)
+    got = torch.full((max(nb, 1), 2), -1, dtype=torch.int64, device=DEV)
+    n_bad = torch.full((1,), -1, dtype=torch.int64, device=DEV)
+    bad = torch.full((cap + 1,), -1, dtype=torch.int64, device=DEV)
+    diffs = torch.full((cap + 1, 2), -1, dtype=torch.int64, device=DEV)
+    ew.ew_verify(snap, nbytes, stored, got, n_bad, bad, diffs, cap, stream())
+    torch.cuda.synchronize()
+    o_bad, o_diffs = checksum.verify(host, stored.cpu().numpy().view(np.uint64)[:nb])
+    assert np.array_equal(stored.cpu().numpy().view(np.uint64)[:nb], checksum.block_checksums(raw))
+    assert int(n_bad.item()) == len(o_bad)
+    m = min(len(o_bad), cap)
+    assert bad.cpu().numpy()[:m].tolist() == o_bad[:m].tolist()
+    assert np.array_equal(diffs.cpu().numpy().view(np.uint64)[:m], o_diffs[:m])
+    assert bad.cpu().numpy()[m:].tolist() == [-1] * (cap + 1 - m), "bad-block list written past the count/cap"
+    if nb:
+        assert np.array_equal(got.cpu().numpy().view(np.uint64)[:nb], checksum.block_checksums(host))
+    return o_bad, o_diffs
+
+
+def test_verify_clean_and_single_flip():
+    rng = np.random.default_rng(42)
+    nbytes = 21 * MIB + 4096 + 5
+    bad, _ = verify_case(nbytes, [], rng)
+    assert len(bad) == 0
+    for _ in range(4):
+        o, bit = int(rng.integers(0, nbytes)), int(rng.integers(0, 8))
+        bad, diffs = verify_case(nbytes, [(o, bit)], rng)
+        assert bad.tolist() == [o >> 20]
+        assert int(diffs[0, 1]) == 1 << (8 * (o % 8) + bit)
+
+
+def test_verify_many_flips_ordered_and_capped():
+    rng = np.random.default_rng(43)
+    nbytes = 2100 * MIB // 100  # 21 MiB
+    flips = [(b * MIB + int(rng.integers(0, MIB)), int(rng.integers(0, 8))) for b in (20, 3, 11, 0, 7, 15)]
+    bad, _ = verify_case(nbytes, flips, rng)
+    assert bad.tolist() == [0, 3, 7, 11, 15, 20]
+    verify_case(nbytes, flips, rng, cap=4)
+    verify_case(nbytes, flips, rng, cap=0)
+    verify_case(0, [], rng)
+    # more blocks than one compare pass (1024 threads) with flips in several passes
+    nbytes = 2500 * MIB
+    big = [(b * MIB + 17, 1) for b in (5, 1023, 1024, 2047, 2048, 2499)]
+    bad, _ = verify_case(nbytes, big, rng)
+    assert bad.tolist() == [5, 1023, 1024, 2047, 2048, 2499]
+
+
+# ------------------------------------------------------------------ pack / unpack
+def reshard_case(old_dp, new_dp, mask, numel, chunk, elem_size, rng, tile_elems=0):
+    starts = layout.unit_starts(numel, chunk)
+    alive = layout.alive_list(old_dp, mask)
+    lens = layout.shard_lengths(starts, old_dp)
+    data = random_shards(lens, elem_size, rng)   # the true content of every old rank's partition
+    poison = 0xDEAD if elem_size == 2 else 0xDEADBEEF
+    o_shards = [d if alive[j] else None for j, d in enumerate(data)]
+    o_snaps = [None if alive[j] else d for j, d in enumerate(data)]
+    want_new = layout.reshard(o_shards, o_snaps, old_dp, new_dp, mask, starts)
+    want_stage, want_table = layout.staging(o_shards, o_snaps, old_dp, new_dp, mask, starts)
+
+    # device: failed ranks' live shards are poisoned, alive ranks have no snapshot at all
+    old_dev = [to_dev(d if alive[j] else np.full_like(d, poison), elem_size) for j, d in enumerate(data)]
+    snap_dev = [None if alive[j] else to_dev(d, elem_size) for j, d in enumerate(data)]
+    plan = ew.ew_plan(old_dp, new_dp, mask, numel, chunk)
+    stage, new = run_reshard(plan, old_dev, snap_dev, elem_size, tile_elems)
+
+    assert plan.stage_len == len(want_stage)
+    assert np.array_equal(np_bits(stage[:plan.stage_len]), want_stage), "staging arena differs"
+    assert guard_intact(stage, plan.stage_len, elem_size)
+    for (h, k), (off, n) in want_table.items():
+        assert (plan.pair_off(h, k), plan.pair_len(h, k)) == (off, n)
+    for k in range(new_dp):
+        n = plan.new_shard_len(k)
+        assert n == len(want_new[k])
+        assert np.array_equal(np_bits(new[k][:n]), want_new[k]), f"new shard {k} differs"
+        assert guard_intact(new[k], n, elem_size)
+    plan.close()
+
+
+def recoverable_masks(old_dp):
+    return [m for m in range(1, 1 << old_dp)
+            if all((m >> j) & 1 or (m >> ((j - 1) % old_dp)) & 1 for j in range(old_dp))]
+
+
+@pytest.mark.parametrize("elem_size", [2, 4])
+def test_reshard_small_exhaustive(elem_size):
+    rng = np.random.default_rng(elem_size)
+    for Do in range(1, 5):
+        for Dn in range(1, 5):
+            for mask in recoverable_masks(Do):
+                for N, C in ((0, 8), (1, 1), (9, 8), (64, 24), (1000, 24), (1000, 100), (4099, 264), (4099, 5000)):
+                    reshard_case(Do, Dn, mask, N, C, elem_size, rng)
+
+
+@pytest.mark.parametrize("elem_size", [2, 4])
+@pytest.mark.parametrize("case", [
+    (4, 3, 0b1011, 1 << 20, 4096),            # the paper's scenario at the Tiny workload's size
+    (8, 7, 0xFF & ~(1 << 5), 3_000_000 + 8 * 37, 262144),   # several tiles per segment, ragged tail unit
+    (7, 8, 0x7F, 2_000_000, 65536),           # scale-up with a joiner
+    (16, 12, 0xFFFF & ~0b0101001000000010, 1_500_000 + 104, 4096),  # 4 failures
+    (6, 4, 0b111111, 999_999, 10_007),        # voluntary shrink, nothing aligned
+    (3, 3, 0b101, 500_000, 50_000),           # same degree, one rank replaced from its snapshot
+    (5, 9, 0b10101, 800_000, 800_000),        # one unit, two failures, growth
+])
+def test_reshard_medium(case, elem_size):
+    rng = np.random.default_rng(hash(case) & 0xFFFF)
+    reshard_case(*case, elem_size, rng)
+
+
+@pytest.mark.parametrize("tile_elems,wgs", [(64, 0), (1000, 1), (4096, 8), (8192, 0), (65536, 4), (1 << 20, 2)])
+def test_reshard_launch_shapes(tile_elems, wgs):
+    ew.ew_set_param("copy_wgs_per_cu", wgs)
+    rng = np.random.default_rng(tile_elems)
+    for es in (2, 4):
+        reshard_case(8, 7, 0xFF & ~(1 << 5), 3_000_000 + 8 * 37, 262144, es, rng, tile_elems)
+        reshard_case(6, 4, 0b111011, 999_999, 10_007, es, rng, tile_elems)
+
+
+def test_null_buffers_are_rejected():
+    plan = ew.ew_plan(4, 3, 0b1011, 1 << 16, 4096)
+    ew.ew_plan_upload(plan, 0, stream())
+    old = [torch.zeros(plan.old_shard_len(j), dtype=torch.int32, device=DEV) for j in range(4)]
+    stage = torch.zeros(plan.stage_len, dtype=torch.int32, device=DEV)
+    with pytest.raises(ew.EwError) as e:   # rank 2 failed and no snapshot of it was passed
+        ew.ew_pack(plan, old, [None] * 4, stage, 4, stream())
+    assert e.value.code == ew.EW_EINVAL
+    with pytest.raises(ew.EwError):
+        ew.ew_pack(plan, old, [None, None, old[2], None], stage, 3, stream())
+    with pytest.raises(ValueError):        # binding refuses a short arena before any launch
+        ew.ew_pack(plan, old, [None, None, old[2], None], stage[:-8], 4, stream())
+    # failed rank's live shard may be NULL: it is never read
+    ew.ew_pack(plan, [old[0], old[1], None, old[3]], [None, None, old[2], None], stage, 4, stream())
+    torch.cuda.synchronize()

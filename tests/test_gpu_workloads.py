@@ -1,0 +1,178 @@
+"""The five named workloads at full size on the GPU, in the launch configuration bench.py times
+(library defaults), against the CPU oracle.
+
+  tiny, 7b_stage      every array compared element by element with the oracle's result
+  7b_rank_snapshot    snapshot bytes + every checksum record against the oracle; one flipped bit
+                      must be located (block index and bit lane)
+  13b_stage, 70b_stage  bf16 array compared element by element; for the fp32 arrays, sampled
+                      elements of every new shard (incl. both ends) are recomputed one by one by
+                      the oracle's locator from the seeded generator, and the multiset of 64-bit
+                      words is shown to be conserved (wrapping sums of w and w*w, torch integer ops)
+"""
+import gc
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2510_00606_amd as ew
+from oracle import checksum, layout
+from paper_2510_00606_amd import configs, synth
+
+from gpu_util import DEV, stream
+
+pytestmark = pytest.mark.gpu
+
+
+def free():
+    gc.collect()
+    torch.cuda.empty_cache()
+
+
+def word_moments(tensors):
+    """Wrapping sums of the 64-bit words and of their squares over a list of device tensors."""
+    s1 = s2 = 0
+    for t in tensors:
+        if t.numel() == 0:
+            continue
+        w = t.view(torch.int64)
+        s1 = (s1 + int(w.sum().item())) & ((1 << 64) - 1)
+        s2 = (s2 + int((w * w).sum().item())) & ((1 << 64) - 1)
+    return s1, s2
+
+
+def run_workload_array(w, arr, plan, starts, full_compare, snapshot_all):
+    es = synth.ELEM_SIZE[arr]
+    alive = layout.alive_list(w.old_dp, w.alive_mask)
+    st = stream()
+    old = [synth.fill(w.seed, j, arr, 0, plan.old_shard_len(j), DEV) for j in range(w.old_dp)]
+    # per-step snapshot (ring placement: the copy of rank j's partition lives with rank j-1)
+    snaps, sums = [None] * w.old_dp, [None] * w.old_dp
+    for j in range(w.old_dp):
+        if snapshot_all or not alive[j]:
+            nbytes = old[j].numel() * es
+            snaps[j] = torch.empty_like(old[j])
+            sums[j] = torch.zeros((ew.num_blocks(nbytes), 2), dtype=torch.int64, device=DEV)
+            ew.ew_snapshot(old[j], snaps[j], nbytes, sums[j], st)
+    torch.cuda.synchronize()
+    host_old = [synth.to_numpy_bits(t) for t in old] if full_compare else None
+    src_moments = word_moments(old)
+    # failure: the device memory of failed ranks is gone
+    for j in w.failed:
+        old[j].view(torch.uint8).fill_(0xFF)
+    # integrity check of the snapshots that will be read
+    for j in w.failed:
+        nbytes = snaps[j].numel() * es
+        got = torch.zeros_like(sums[j])
+        n_bad = torch.zeros(1, dtype=torch.int64, device=DEV)
+        bad = torch.zeros(8, dtype=torch.int64, device=DEV)
+        diffs = torch.zeros((8, 2), dtype=torch.int64, device=DEV)
+        ew.ew_verify(snaps[j], nbytes, sums[j], got, n_bad, bad, diffs, 8, st)
+        assert int(n_bad.item()) == 0
+    stage = torch.empty(plan.stage_len, dtype=old[0].dtype, device=DEV)
+    new = [torch.empty(plan.new_shard_len(k), dtype=old[0].dtype, device=DEV) for k in range(w.new_dp)]
+    for t in new:
+        t.view(torch.uint8).fill_(0x5A)
+    ew.ew_pack(plan, old, snaps, stage, es, st)
+    ew.ew_unpack(plan, stage, old, snaps, new, es, st)
+    torch.cuda.synchronize()
+
+    # (1) the multiset of words is conserved
+    assert word_moments(new) == src_moments
+    # (2) sampled elements, recomputed one by one from the generator through the oracle's locator
+    rng = np.random.default_rng([w.seed, synth.ARRAYS.index(arr)])
+    for k in range(w.new_dp):
+        n = plan.new_shard_len(k)
+        offs = np.unique(np.concatenate([np.arange(min(n, 64)), np.arange(max(0, n - 64), n),
+                                         rng.integers(0, n, 1 << 16)]))
+        _, owner, ooff = layout.locate_new_elements(starts, w.old_dp, w.new_dp, k, offs)
+        want = np.empty(len(offs), dtype={2: np.uint16, 4: np.uint32}[es])
+        for j in range(w.old_dp):
+            m = owner == j
+            if m.any():
+                want[m] = synth.to_numpy_bits(synth.values_at(w.seed, j, arr, torch.from_numpy(ooff[m])))
+        got = synth.to_numpy_bits(new[k][torch.from_numpy(offs).to(DEV)])
+        assert np.array_equal(got, want), f"{w.name} {arr}: sampled elements of new shard {k} differ"
+    # (3) everything, element by element
+    if full_compare:
+        o_sh = [h if alive[j] else None for j, h in enumerate(host_old)]
+        o_sn = [None if alive[j] else h for j, h in enumerate(host_old)]
+        flat = layout.reconstruct_flat(o_sh, o_sn, w.old_dp, alive, starts)
+        want_new = layout.slice_flat(flat, w.new_dp, starts)
+        for k in range(w.new_dp):
+            assert np.array_equal(synth.to_numpy_bits(new[k]), want_new[k]), f"{w.name} {arr}: new shard {k} differs"
+        del want_new, flat
+    del old, snaps, stage, new
+    free()
+
+
+def run_workload(name, full_arrays, snapshot_all):
+    w = configs.ALL[name]()
+    starts = w.unit_starts()
+    plan = ew.ew_plan_bounds(w.old_dp, w.new_dp, w.alive_mask, starts)
+    ew.ew_plan_upload(plan, 0, stream())
+    s64 = starts.astype(np.int64)
+    for arr in synth.ARRAYS:
+        print(f"[{name}] array {arr}", flush=True)
+        run_workload_array(w, arr, plan, s64, arr in full_arrays, snapshot_all)
+    plan.close()
+
+
+def test_tiny_all_arrays():
+    run_workload("tiny", synth.ARRAYS, True)
+
+
+@pytest.mark.timeout(900)
+def test_7b_stage_all_arrays():
+    run_workload("7b_stage", synth.ARRAYS, True)
+
+
+@pytest.mark.timeout(900)
+def test_13b_stage():
+    run_workload("13b_stage", ("P",), True)
+
+
+@pytest.mark.timeout(900)
+def test_70b_stage():
+    run_workload("70b_stage", ("P",), False)
+
+
+@pytest.mark.timeout(600)
+def test_7b_rank_snapshot_and_bit_flip():
+    w = configs.snapshot_7b()
+    rng = np.random.default_rng([w.seed, 99])
+    flip_arr = synth.ARRAYS[int(rng.integers(0, 4))]
+    st = stream()
+    for arr in synth.ARRAYS:
+        es = synth.ELEM_SIZE[arr]
+        nbytes = w.numel * es
+        src = synth.fill(w.seed, 0, arr, 0, w.numel, DEV)
+        snap = torch.empty_like(src)
+        nb = ew.num_blocks(nbytes)
+        assert nb == {2: 418, 4: 835}[es]
+        sums = torch.zeros((nb, 2), dtype=torch.int64, device=DEV)
+        ew.ew_snapshot(src, snap, nbytes, sums, st)
+        torch.cuda.synchronize()
+        assert torch.equal(src.view(torch.int16), snap.view(torch.int16))
+        host = synth.to_numpy_bits(src)
+        want = checksum.block_checksums(host)
+        assert np.array_equal(sums.cpu().numpy().view(np.uint64), want)
+        if arr == flip_arr:
+            o, bit = int(rng.integers(0, nbytes)), int(rng.integers(0, 8))
+            snap.view(torch.uint8)[o] ^= (1 << bit)
+            got = torch.zeros_like(sums)
+            n_bad = torch.zeros(1, dtype=torch.int64, device=DEV)
+            bad = torch.full((4,), -1, dtype=torch.int64, device=DEV)
+            diffs = torch.zeros((4, 2), dtype=torch.int64, device=DEV)
+            ew.ew_verify(snap, nbytes, sums, got, n_bad, bad, diffs, 4, st)
+            torch.cuda.synchronize()
+            assert int(n_bad.item()) == 1
+            assert int(bad[0].item()) == o >> 20
+            d = diffs.cpu().numpy().view(np.uint64)[0]
+            assert int(d[1]) == 1 << (8 * (o % 8) + bit)          # bit lane inside the 64-bit word
+            hb = host.view(np.uint8).copy()
+            hb[o] ^= np.uint8(1 << bit)
+            o_bad, o_diffs = checksum.verify(hb, want)
+            assert o_bad.tolist() == [o >> 20] and np.array_equal(o_diffs[0], d)
+        del src, snap
+        free()

@@ -1,0 +1,235 @@
+"""Host-side tests (no GPU): the C-ABI library loads and exports what include/elaswave.h
+declares; ew_plan's segment table satisfies the invariants of the transfer plan and induces
+exactly the oracle's element map; error paths."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2510_00606_amd as ew
+from oracle import brute, layout
+from paper_2510_00606_amd import binding, configs
+
+
+def recoverable_masks(old_dp):
+    out = []
+    for m in range(1, 1 << old_dp):
+        alive = [(m >> j) & 1 for j in range(old_dp)]
+        if all(alive[j] or alive[(j - 1) % old_dp] for j in range(old_dp)):
+            out.append(m)
+    return out
+
+
+# ------------------------------------------------------------------ boundary
+def test_library_exports_every_declared_symbol(repo_root):
+    hdr = open(os.path.join(repo_root, "include", "elaswave.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(ew_[a-z0-9_]+)\s*\(", hdr))
+    assert {"ew_plan", "ew_pack", "ew_unpack", "ew_snapshot", "ew_verify", "ew_plan_bounds"} <= declared
+    handle = ctypes.CDLL(binding.LIB_PATH)
+    for name in sorted(declared):
+        assert hasattr(handle, name), f"{name} declared in elaswave.h but not exported"
+    assert declared == set(binding.EXPORTS), "binding and header disagree"
+    assert "gfx950" in ew.ew_version()
+
+
+def test_seg_struct_layout_matches_header():
+    assert binding.SEG_DTYPE.itemsize == 40
+    assert binding.CKSUM_DTYPE.itemsize == 16
+
+
+# ------------------------------------------------------------------ errors
+def test_error_codes():
+    def code(*a):
+        with pytest.raises(ew.EwError) as e:
+            ew.ew_plan(*a)
+        return e.value.code
+
+    assert code(0, 3, 0, 100, 10) == ew.EW_EINVAL
+    assert code(4, 0, 0b1111, 100, 10) == ew.EW_EINVAL
+    assert code(65, 3, 1, 100, 10) == ew.EW_EINVAL
+    assert code(4, 3, 0b1111, 100, 0) == ew.EW_EINVAL
+    assert code(4, 3, 0b11111, 100, 10) == ew.EW_EINVAL        # bit above old_dp
+    assert code(4, 3, 0, 100, 10) == ew.EW_EUNRECOVERABLE      # no survivor
+    assert code(4, 3, 0b1001, 100, 10) == ew.EW_EUNRECOVERABLE  # 1 and 2 failed: 2's holder is 1
+    assert code(1, 1, 0, 100, 10) == ew.EW_EUNRECOVERABLE
+    with pytest.raises(ew.EwError) as e:
+        ew.ew_plan_bounds(2, 2, 3, [0, 10, 5])
+    assert e.value.code == ew.EW_EINVAL
+    with pytest.raises(ew.EwError) as e:
+        ew.ew_plan_bounds(2, 2, 3, [1, 10])
+    assert e.value.code == ew.EW_EINVAL
+    assert "unrecoverable" in ew.ew_strerror(ew.EW_EUNRECOVERABLE)
+    # not uploaded: pack/unpack refuse before touching any buffer
+    p = ew.ew_plan(4, 3, 0b1011, 4096, 512)
+    with pytest.raises(ew.EwError) as e:
+        ew.ew_pack(p, [1, 1, 0, 1], [0, 0, 1, 0], 1, 4)
+    assert e.value.code == ew.EW_EINVAL
+    with pytest.raises(ew.EwError):
+        ew.ew_set_param("no_such_knob", 1)
+    with pytest.raises(ew.EwError):
+        ew.ew_set_param("cksum_sub_bytes", 3000)
+
+
+def test_max_degree_and_wide_mask():
+    p = ew.ew_plan(64, 63, (1 << 64) - 1 - (1 << 63), 64 * 63 * 8 * 3, 64 * 63 * 8)
+    assert p.holder_of(63) == 62 and p.new_rank_of(63) == -1
+    assert sum(p.new_shard_len(k) for k in range(63)) == p.numel
+
+
+# ------------------------------------------------------------------ invariants of the table
+def check_invariants(p: ew.Plan, old_dp, new_dp, mask, numel):
+    segs = p.segs()
+    alive = [(mask >> j) & 1 for j in range(old_dp)]
+    nro = [p.new_rank_of(j) for j in range(old_dp)]
+    assert int(segs["len"].sum()) == numel == p.numel
+    assert (segs["len"] > 0).all()
+    old_len = [p.old_shard_len(j) for j in range(old_dp)]
+    new_len = [p.new_shard_len(k) for k in range(new_dp)]
+    assert sum(old_len) == sum(new_len) == numel
+    # membership
+    for s in segs:
+        j, h, k = int(s["src_owner"]), int(s["holder"]), int(s["dst_rank"])
+        assert alive[h]
+        assert bool(s["flags"] & ew.EW_SEG_SNAPSHOT) == (not alive[j])
+        assert h == (j if alive[j] else (j - 1) % old_dp) == p.holder_of(j)
+        assert bool(s["flags"] & ew.EW_SEG_LOCAL) == (nro[h] == k)
+        assert (s["stage_off"] == ew.EW_NO_STAGE) == bool(s["flags"] & ew.EW_SEG_LOCAL)
+    # segments tile every new shard and every old shard exactly
+    for key_rank, key_off, lens in (("dst_rank", "dst_off", new_len), ("src_owner", "src_off", old_len)):
+        for r, n in enumerate(lens):
+            sel = segs[segs[key_rank] == r]
+            order = np.argsort(sel[key_off], kind="stable")
+            off, ln = sel[key_off][order].astype(np.int64), sel["len"][order].astype(np.int64)
+            assert int(ln.sum()) == n
+            if n:
+                assert off[0] == 0 and (off[1:] == off[:-1] + ln[:-1]).all()
+    # arena: contiguous pair messages sorted by (dst, holder); segments fill each message in order
+    rem = segs[(segs["flags"] & ew.EW_SEG_LOCAL) == 0]
+    assert int(rem["len"].sum()) == p.stage_len == p.remote_elems
+    expect_off = 0
+    for k in range(new_dp):
+        for h in range(old_dp):
+            n = p.pair_len(h, k)
+            sel = rem[(rem["holder"] == h) & (rem["dst_rank"] == k)]
+            assert int(sel["len"].sum()) == n
+            if n:
+                assert p.pair_off(h, k) == expect_off
+                so, ln = sel["stage_off"].astype(np.int64), sel["len"].astype(np.int64)
+                assert so[0] == expect_off and (so[1:] == so[:-1] + ln[:-1]).all()
+                expect_off += n
+    # balance: shard lengths within one granule per unit of each other is implied by the layout;
+    # here: identical to the oracle's lengths (checked by the caller)
+    return segs
+
+
+def induced_map(segs, new_len):
+    """(new rank, new offset) -> (owner, old offset, snapshot?, holder, stage position or -1)."""
+    out = [[None] * n for n in new_len]
+    for s in segs:
+        k = int(s["dst_rank"])
+        local = bool(s["flags"] & ew.EW_SEG_LOCAL)
+        for i in range(int(s["len"])):
+            slot = int(s["dst_off"]) + i
+            assert out[k][slot] is None, "element written twice"
+            out[k][slot] = (int(s["src_owner"]), int(s["src_off"]) + i, bool(s["flags"] & ew.EW_SEG_SNAPSHOT),
+                            int(s["holder"]), -1 if local else int(s["stage_off"]) + i)
+    assert all(x is not None for row in out for x in row), "element never written"
+    return out
+
+
+def check_against_brute(old_dp, new_dp, mask, numel, chunk):
+    p = ew.ew_plan(old_dp, new_dp, mask, numel, chunk)
+    starts = layout.unit_starts(numel, chunk)
+    assert [p.old_shard_len(j) for j in range(old_dp)] == layout.shard_lengths(starts, old_dp)
+    assert [p.new_shard_len(k) for k in range(new_dp)] == layout.shard_lengths(starts, new_dp)
+    segs = check_invariants(p, old_dp, new_dp, mask, numel)
+    alive = layout.alive_list(old_dp, mask)
+    emap, new_len = brute.reshard_map(starts, old_dp, new_dp, alive)
+    got = induced_map(segs, new_len)
+    nro = layout.new_rank_of(old_dp, new_dp, alive)
+    assert [p.new_rank_of(j) for j in range(old_dp)] == nro
+    # arena positions by the oracle's rule: pairs sorted by (dst, holder), ascending element order
+    pos, cur = {}, 0
+    for k in range(new_dp):
+        for h in range(old_dp):
+            for e, (j, oo, snap, holder, kk, no) in enumerate(emap):
+                if holder == h and kk == k and nro[h] != k:
+                    pos[e] = cur
+                    cur += 1
+    for e, (j, oo, snap, holder, k, no) in enumerate(emap):
+        assert got[k][no] == (j, oo, snap, holder, pos.get(e, -1))
+    # explicit-boundary entry point builds the same table
+    q = ew.ew_plan_bounds(old_dp, new_dp, mask, starts)
+    assert q.segs().tobytes() == segs.tobytes()
+
+
+def test_table_equals_brute_force_small():
+    n = 0
+    for Do in range(1, 6):
+        for Dn in range(1, 6):
+            for mask in recoverable_masks(Do):
+                for N in (0, 1, 7, 8, 9, 64):
+                    for C in sorted({1, 8, 24, 100, max(N, 1), N + 1}):
+                        check_against_brute(Do, Dn, mask, N, C)
+                        n += 1
+    assert n > 4000
+
+
+def test_table_equals_brute_force_ragged():
+    for Do in range(1, 7):
+        masks = recoverable_masks(Do)
+        for Dn in range(1, 7):
+            for mask in {masks[-1], masks[0], masks[len(masks) // 2]}:
+                for N, C in ((1000, 24), (1000, 100), (4099, 264), (4099, 4099), (4099, 5000)):
+                    check_against_brute(Do, Dn, mask, N, C)
+
+
+def test_paper_scenario_pairs():
+    # D = 4, F = {2} (Sec. 5.2, Fig. 7): golden per-unit cells, see tests/golden/live_remap_d4_f2.txt
+    rows = [l.split()[1:] for l in open(os.path.join(os.path.dirname(__file__), "golden", "live_remap_d4_f2.txt"))
+            if l.startswith("B ")]
+    p = ew.ew_plan(4, 3, 0b1011, 1 << 20, 4096)
+    segs = p.segs()
+    cells = {}
+    for s in segs:
+        key = (int(s["src_owner"]), "snap" if s["flags"] & ew.EW_SEG_SNAPSHOT else "live", int(s["holder"]),
+               int(s["dst_rank"]), "local" if s["flags"] & ew.EW_SEG_LOCAL else "remote")
+        cells[key] = cells.get(key, 0) + int(s["len"])
+    want = {(int(o), kind, int(h), int(dn), loc): int(n) * 256 for o, kind, h, do, dn, loc, n in rows}
+    assert cells == want
+    assert p.pair_len(1, 0) == 336 * 256 and p.pair_len(1, 2) == 344 * 256
+    assert not (segs["holder"] == 2).any()
+
+
+@pytest.mark.parametrize("name", ["7b_stage", "13b_stage", "70b_stage"])
+def test_full_size_plans_are_consistent(name):
+    w = configs.ALL[name]()
+    starts = w.unit_starts()
+    p = ew.ew_plan_bounds(w.old_dp, w.new_dp, w.alive_mask, starts)
+    segs = p.segs()
+    assert int(segs["len"].sum()) == w.numel
+    nb = layout._bounds_matrix(starts.astype(np.int64), w.new_dp)
+    ob = layout._bounds_matrix(starts.astype(np.int64), w.old_dp)
+    assert [p.new_shard_len(k) for k in range(w.new_dp)] == (nb[:, 1:] - nb[:, :-1]).sum(axis=0).tolist()
+    assert [p.old_shard_len(j) for j in range(w.old_dp)] == (ob[:, 1:] - ob[:, :-1]).sum(axis=0).tolist()
+    # every boundary is on the 8-element granule for these shapes: 128-bit aligned everywhere
+    for f in ("src_off", "dst_off", "len"):
+        assert (segs[f] % 8 == 0).all()
+    rem = segs[(segs["flags"] & ew.EW_SEG_LOCAL) == 0]
+    assert (rem["stage_off"] % 8 == 0).all()
+    # sampled elements of every new shard: table agrees with the oracle's one-by-one locator
+    rng = np.random.default_rng(w.seed)
+    for k in range(w.new_dp):
+        sel = segs[segs["dst_rank"] == k]
+        order = np.argsort(sel["dst_off"])
+        sel = sel[order]
+        offs = np.sort(rng.integers(0, p.new_shard_len(k), 4000))
+        glob, owner, ooff = layout.locate_new_elements(starts.astype(np.int64), w.old_dp, w.new_dp, k, offs)
+        i = np.searchsorted(sel["dst_off"].astype(np.int64), offs, side="right") - 1
+        assert (sel["src_owner"][i] == owner).all()
+        assert (sel["src_off"][i].astype(np.int64) + (offs - sel["dst_off"][i].astype(np.int64)) == ooff).all()
+    if name == "70b_stage":
+        assert abs(p.stage_len / w.numel - 0.5) < 1e-4  # D -> D+1 closed form: half stays local
