@@ -1,0 +1,262 @@
+#!/usr/bin/env python3
+"""Benchmark of the whole hot path on one MI355X.
+
+One step = one pass over one DP group's state (all four arrays P/W/M/V resident in HBM):
+  a1 plan      ew_plan_bounds + ew_plan_upload (host, counted in the step time)
+  a2 snapshot  ew_snapshot of every old rank's partition (copy + per-MiB checksums)
+  a3 verify    ew_verify of the snapshots that replace failed ranks
+  a4 pack      ew_pack   (non-local segments -> staging arena)
+  a6 unpack    ew_unpack (arena + local segments -> new shards)
+  a7 snapshot  ew_snapshot of every new rank's partition
+`value` is the algorithmic bytes (read + written) of a2..a7 divided by the step's wall time.
+
+Prints ONE JSON line.  --gpus above 1 is refused: this build is one GPU only.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="7b_stage", choices=["tiny", "7b_stage", "13b_stage"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-units", type=int, default=768)
+    return ap.parse_args()
+
+
+def read_traffic(kernel_key):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE / WRITE_SIZE runs); None when no summary for this workload exists."""
+    path = os.path.join(ROOT, "profiles", "pmc_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        t = line.split()
+        if len(t) >= 2 and t[0] == kernel_key:
+            try:
+                return float(t[1])
+            except ValueError:
+                return None
+    return None
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (all simulated DP ranks live in one MI355X's HBM); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2510_00606_amd as ew
+    from paper_2510_00606_amd import configs, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; there is no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    st = torch.cuda.current_stream().cuda_stream
+    w = configs.ALL[args.workload]()
+    starts = w.unit_starts()
+
+    # ---------------- setup (untimed): state resident in HBM
+    plan0 = ew.ew_plan_bounds(w.old_dp, w.new_dp, w.alive_mask, starts)
+    alive = [(w.alive_mask >> j) & 1 for j in range(w.old_dp)]
+    old_len = [plan0.old_shard_len(j) for j in range(w.old_dp)]
+    new_len = [plan0.new_shard_len(k) for k in range(w.new_dp)]
+    stage_len = plan0.stage_len
+    plan0.close()
+    A = synth.ARRAYS
+    es = synth.ELEM_SIZE
+    old = {a: [synth.fill(w.seed, j, a, 0, old_len[j], dev) for j in range(w.old_dp)] for a in A}
+    snap = {a: [torch.empty_like(t) for t in old[a]] for a in A}
+    sums = {a: [torch.zeros((ew.num_blocks(n * es[a]), 2), dtype=torch.int64, device=dev) for n in old_len] for a in A}
+    stage = {a: torch.empty(stage_len, dtype=synth.TORCH_DTYPE[a], device=dev) for a in A}
+    new = {a: [torch.empty(n, dtype=synth.TORCH_DTYPE[a], device=dev) for n in new_len] for a in A}
+    nsnap = {a: [torch.empty_like(t) for t in new[a]] for a in A}
+    nsums = {a: [torch.zeros((ew.num_blocks(n * es[a]), 2), dtype=torch.int64, device=dev) for n in new_len] for a in A}
+    got = {a: [torch.zeros_like(t) for t in sums[a]] for a in A}
+    n_bad = torch.zeros(1, dtype=torch.int64, device=dev)
+    bad = torch.zeros(16, dtype=torch.int64, device=dev)
+    diffs = torch.zeros((16, 2), dtype=torch.int64, device=dev)
+    # after the failure the failed ranks' device memory is not available to pack/unpack
+    old_after = {a: [t if alive[j] else None for j, t in enumerate(old[a])] for a in A}
+    snap_used = {a: [None if alive[j] else t for j, t in enumerate(snap[a])] for a in A}
+    torch.cuda.synchronize()
+
+    numel = w.numel
+    n_remote = stage_len
+    bytes_phase = {
+        "snapshot_old": sum(2 * n * 14 for n in old_len) + 16 * sum(int(t.shape[0]) for a in A for t in sums[a]),
+        "verify": sum(old_len[j] * 14 for j in w.failed),
+        "pack": 2 * 14 * n_remote,
+        "unpack": 2 * 14 * numel,
+        "snapshot_new": sum(2 * n * 14 for n in new_len) + 16 * sum(int(t.shape[0]) for a in A for t in nsums[a]),
+    }
+    launches = {"snapshot_old": 4 * w.old_dp, "verify": 4 * len(w.failed), "pack": 4, "unpack": 4,
+                "snapshot_new": 4 * w.new_dp}
+    step_bytes = sum(bytes_phase.values())
+    phases = list(bytes_phase)
+
+    def step(record):
+        ev = []
+
+        def mark():
+            if record:
+                e = torch.cuda.Event(enable_timing=True)
+                e.record()
+                ev.append(e)
+
+        t0 = time.perf_counter()
+        plan = ew.ew_plan_bounds(w.old_dp, w.new_dp, w.alive_mask, starts)          # a1
+        ew.ew_plan_upload(plan, 0, st)
+        t_plan = time.perf_counter() - t0
+        mark()
+        for a in A:                                                                    # a2
+            for j in range(w.old_dp):
+                ew.ew_snapshot(old[a][j], snap[a][j], old_len[j] * es[a], sums[a][j], st)
+        mark()
+        for a in A:                                                                    # a3
+            for j in w.failed:
+                ew.ew_verify(snap[a][j], old_len[j] * es[a], sums[a][j], got[a][j], n_bad, bad, diffs, 16, st)
+        mark()
+        for a in A:                                                                    # a4
+            ew.ew_pack(plan, old_after[a], snap_used[a], stage[a], es[a], st)
+        mark()
+        for a in A:                                                                    # a6
+            ew.ew_unpack(plan, stage[a], old_after[a], snap_used[a], new[a], es[a], st)
+        mark()
+        for a in A:                                                                    # a7
+            for k in range(w.new_dp):
+                ew.ew_snapshot(new[a][k], nsnap[a][k], new_len[k] * es[a], nsums[a][k], st)
+        mark()
+        return plan, t_plan, ev
+
+    plans = []
+    for _ in range(args.warmup):
+        p, _, _ = step(False)
+        plans.append(p)
+    torch.cuda.synchronize()
+    for p in plans:
+        p.close()
+    plans = []
+
+    # ---------------- timed region: exactly K steps
+    records = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        p, t_plan, ev = step(True)
+        plans.append(p)          # freed after the region: the kernels that use its tables are in flight
+        records.append((t_plan, ev))
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    for p in plans:
+        p.close()
+    assert int(n_bad.item()) == 0, "verification of an intact snapshot reported bad blocks"
+
+    ms_per_step = elapsed / args.steps * 1e3
+    value = step_bytes / (elapsed / args.steps) / 1e9
+    phase_ms = {ph: 0.0 for ph in phases}
+    for _, ev in records:
+        for i, ph in enumerate(phases):
+            phase_ms[ph] += ev[i].elapsed_time(ev[i + 1])
+    for ph in phases:
+        phase_ms[ph] /= args.steps
+    plan_ms = sum(r[0] for r in records) / args.steps * 1e3
+    kernels = {}
+    for ph in phases:
+        if phase_ms[ph] > 0:
+            gbs = bytes_phase[ph] / phase_ms[ph] / 1e6
+            kernels[ph] = {"ms": round(phase_ms[ph], 4), "launches": launches[ph], "GB": round(bytes_phase[ph] / 1e9, 4),
+                           "GB/s": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4)}
+    # dominant kernel by traffic and time: the snapshot copy+checksum kernel (a2 and a7 launches)
+    snap_bytes = bytes_phase["snapshot_old"] + bytes_phase["snapshot_new"]
+    snap_ms = phase_ms["snapshot_old"] + phase_ms["snapshot_new"]
+    snap_launches = launches["snapshot_old"] + launches["snapshot_new"]
+    achieved = snap_bytes / snap_ms / 1e6
+    roofline = {
+        "kernel": "ew_cksum_kernel<copy> (ew_snapshot)", "bound": "hbm", "achieved": round(achieved, 1),
+        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+        "traffic": read_traffic(f"ew_snapshot/{w.name}"),
+        "bytes_per_launch": round(snap_bytes / snap_launches), "avg_launch_us": round(snap_ms / snap_launches * 1e3, 2),
+    }
+    reshard_ms = plan_ms + phase_ms["pack"] + phase_ms["unpack"]
+
+    out = {
+        "metric": "reshard+snapshot GB/s on one MI355X and % of HBM peak; time to reshard one stage",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u64", "data": "synthetic",
+        "config": {"workload": w.name, "note": w.note, "numel": numel, "state_bytes": 14 * numel, "old_dp": w.old_dp,
+                   "new_dp": w.new_dp, "failed": w.failed, "units": int(len(starts) - 1),
+                   "remote_fraction": round(n_remote / numel, 4), "arrays": "bf16 P + fp32 W, M, V"},
+        "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
+        "reshard_one_stage_ms": round(reshard_ms, 3),
+        "reshard_useful_GBps": round(14 * numel / reshard_ms / 1e6, 1),
+        "plan_ms": round(plan_ms, 3),
+        "step_GB": round(step_bytes / 1e9, 3),
+        "kernels": kernels,
+        "roofline": roofline,
+    }
+
+    # ---------------- CPU baseline: the oracle as it stands, one core, on a bounded sample
+    if not args.no_cpu_baseline:
+        from oracle import checksum as o_ck
+        from oracle import layout as o_lay
+        n_units = min(args.cpu_sample_units, len(starts) - 1)
+        s_starts = starts[:n_units + 1].astype(np.int64)
+        s_numel = int(s_starts[-1])
+        s_old_len = o_lay.shard_lengths(s_starts, w.old_dp)
+        host = {a: [synth.to_numpy_bits(old[a][j][:s_old_len[j]]) for j in range(w.old_dp)] for a in A}
+        torch.cuda.synchronize()
+        al = [bool(x) for x in alive]
+        c0 = time.perf_counter()
+        cpu_bytes = 0
+        for a in A:
+            snaps_h = [h.copy() for h in host[a]]                         # a2: copy ...
+            cks = [o_ck.block_checksums(h) for h in snaps_h]              # ... + checksum
+            cpu_bytes += sum(2 * h.nbytes for h in host[a])
+            for j in w.failed:                                            # a3
+                bad_b, _ = o_ck.verify(snaps_h[j], cks[j])
+                assert len(bad_b) == 0
+                cpu_bytes += snaps_h[j].nbytes
+            new_h = o_lay.reshard([h if al[j] else None for j, h in enumerate(host[a])],   # a4 + a6
+                                  [None if al[j] else s for j, s in enumerate(snaps_h)],
+                                  w.old_dp, w.new_dp, w.alive_mask, s_starts)
+            nsn = [h.copy() for h in new_h]                               # a7
+            _ = [o_ck.block_checksums(h) for h in nsn]
+            cpu_bytes += sum(2 * h.nbytes for h in new_h)
+        cpu_s = time.perf_counter() - c0
+        # pack+unpack traffic of the sample under the same accounting as the GPU figure
+        p_s = ew.ew_plan_bounds(w.old_dp, w.new_dp, w.alive_mask, s_starts.astype(np.uint64))
+        cpu_bytes += 2 * 14 * (s_numel + p_s.stage_len)
+        p_s.close()
+        out["cpu_baseline"] = {
+            "value": round(cpu_bytes / cpu_s / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {n_units} of {len(starts) - 1} units of {w.name} ({s_numel} elements, all four arrays): "
+                      f"numpy oracle snapshot+checksum, verify, reconstruct+slice, snapshot+checksum of the result; "
+                      f"{cpu_s:.1f} s on one host core",
+        }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -100,7 +100,12 @@ uint64_t ew_plan_numel(const ew_plan_t *plan);
 uint32_t ew_plan_old_dp(const ew_plan_t *plan);
 uint32_t ew_plan_new_dp(const ew_plan_t *plan);
 uint64_t ew_plan_num_segs(const ew_plan_t *plan);
-const ew_seg_t *ew_plan_segs(const ew_plan_t *plan); /* borrowed; valid until ew_plan_free  */
+/* The explicit segment table (ew_plan_num_segs entries), expanded from the plan's run-length
+ * form on the first call and cached; borrowed, valid until ew_plan_free; NULL if out of memory.
+ * The hot path never needs it: it is for inspection and tests. */
+const ew_seg_t *ew_plan_segs(const ew_plan_t *plan);
+/* Runs of consecutive equal-length units the plan is stored as (2 for a uniform chunk). */
+uint64_t ew_plan_num_runs(const ew_plan_t *plan);
 uint64_t ew_plan_old_shard_len(const ew_plan_t *plan, uint32_t old_rank); /* elements         */
 uint64_t ew_plan_new_shard_len(const ew_plan_t *plan, uint32_t new_rank); /* elements         */
 int32_t ew_plan_new_rank_of(const ew_plan_t *plan, uint32_t old_rank); /* -1: failed/leaving */
@@ -111,11 +116,29 @@ uint64_t ew_plan_stage_len(const ew_plan_t *plan);                     /* arena 
 uint64_t ew_plan_pair_len(const ew_plan_t *plan, uint32_t holder, uint32_t dst_rank);
 uint64_t ew_plan_pair_off(const ew_plan_t *plan, uint32_t holder, uint32_t dst_rank);
 uint64_t ew_plan_remote_elems(const ew_plan_t *plan); /* == stage_len                        */
-uint64_t ew_plan_num_tiles(const ew_plan_t *plan, int which /*0 pack, 1 unpack*/);
+/* Workgroup-sized copy tiles of ew_pack (which = 0) / ew_unpack (which = 1) for elem_size. */
+uint64_t ew_plan_num_tiles(const ew_plan_t *plan, int which, uint32_t elem_size);
+
+/* Host-side view of the copy tiles, decoded by the same routine the kernels use (inspection and
+ * tests; no GPU needed).  src_buf: 0..63 = live shard of that old rank, 64..127 = snapshot of
+ * that owner, 128 = staging arena.  dst_buf: 0..63 = new shard of that rank, 64 = arena. */
+typedef struct {
+  uint64_t src_off; /* elements */
+  uint64_t dst_off; /* elements */
+  uint32_t len;     /* elements */
+  uint16_t src_buf;
+  uint16_t dst_buf;
+} ew_tile_t;
+/* Writes tiles [first, first+count) of the table for `which` (0 pack, 1 unpack) cut at
+ * tile_elems elements into out[] (host) and the table's tile count into *total (may be NULL). */
+int ew_plan_tiles(const ew_plan_t *plan, int which, uint32_t tile_elems, uint64_t first, uint64_t count,
+                  ew_tile_t *out, uint64_t *total);
 
 /* Builds the copy-tile tables (segments cut into pieces of at most tile_elems elements;
- * 0 = library default) and uploads them to the current device on `stream`.  Must precede
- * ew_pack / ew_unpack.  Calling it again replaces the tables (previous work must be done). */
+ * 0 = library default, 4 KiB worth of elements) for both element sizes and uploads them to the
+ * current device on `stream` (a few KiB for a uniform chunk).  Must precede ew_pack /
+ * ew_unpack.  Calling it again replaces the tables (previous work must be done).
+ * EW_EINVAL if a table would exceed 2^31-1 tiles. */
 int ew_plan_upload(ew_plan_t *plan, uint32_t tile_elems, void *stream);
 
 /* ---- Live Remap step 3, send side: gather into per-destination messages -------------------
@@ -155,7 +178,8 @@ int ew_verify(const void *buf, uint64_t nbytes, const ew_cksum_t *expect, ew_cks
               void *stream);
 
 /* Launch-shape knobs for benchmarking sweeps (process-wide, not thread-safe; defaults are the
- * tuned ones).  Names: "tile_elems", "copy_wgs_per_cu", "cksum_sub_bytes", "cksum_wgs_per_cu".
+ * tuned ones).  Names: "tile_bytes", "tile_elems", "copy_wgs_per_cu", "cksum_sub_bytes",
+ * "cksum_wgs_per_cu".
  * Returns EW_EINVAL for an unknown name or an out-of-range value. */
 int ew_set_param(const char *name, int64_t value);
 int64_t ew_get_param(const char *name);

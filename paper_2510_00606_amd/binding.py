@@ -24,6 +24,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libelaswave
 
 SEG_DTYPE = np.dtype([("src_off", "<u8"), ("dst_off", "<u8"), ("stage_off", "<u8"), ("len", "<u8"),
                       ("src_owner", "<u2"), ("holder", "<u2"), ("dst_rank", "<u2"), ("flags", "<u2")])
+TILE_DTYPE = np.dtype([("src_off", "<u8"), ("dst_off", "<u8"), ("len", "<u4"), ("src_buf", "<u2"), ("dst_buf", "<u2")])
 CKSUM_DTYPE = np.dtype([("sum", "<u8"), ("xr", "<u8")])
 
 
@@ -53,7 +54,10 @@ _SIGNATURES = {
     "ew_plan_pair_len": (C.c_uint64, [C.c_void_p, C.c_uint32, C.c_uint32]),
     "ew_plan_pair_off": (C.c_uint64, [C.c_void_p, C.c_uint32, C.c_uint32]),
     "ew_plan_remote_elems": (C.c_uint64, [C.c_void_p]),
-    "ew_plan_num_tiles": (C.c_uint64, [C.c_void_p, C.c_int]),
+    "ew_plan_num_tiles": (C.c_uint64, [C.c_void_p, C.c_int, C.c_uint32]),
+    "ew_plan_num_runs": (C.c_uint64, [C.c_void_p]),
+    "ew_plan_tiles": (C.c_int, [C.c_void_p, C.c_int, C.c_uint32, C.c_uint64, C.c_uint64, C.c_void_p,
+                                C.POINTER(C.c_uint64)]),
     "ew_plan_upload": (C.c_int, [C.c_void_p, C.c_uint32, C.c_void_p]),
     "ew_pack": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p]),
     "ew_unpack": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p]),
@@ -166,8 +170,20 @@ class Plan:
         if n == 0:
             return np.zeros(0, SEG_DTYPE)
         addr = lib().ew_plan_segs(self.handle)
+        if not addr:
+            raise MemoryError("ew_plan_segs: out of memory")
         buf = (C.c_char * (n * SEG_DTYPE.itemsize)).from_address(addr)
         return np.frombuffer(buf, dtype=SEG_DTYPE).copy()
+
+    def tiles(self, which: int, tile_elems: int) -> np.ndarray:
+        """All copy tiles of the pack (0) / unpack (1) table, decoded on the host."""
+        total = C.c_uint64()
+        _check(lib().ew_plan_tiles(self.handle, which, tile_elems, 0, 0, None, C.byref(total)), "ew_plan_tiles")
+        out = np.zeros(total.value, TILE_DTYPE)
+        if total.value:
+            _check(lib().ew_plan_tiles(self.handle, which, tile_elems, 0, total.value, out.ctypes.data, None),
+                   "ew_plan_tiles")
+        return out
 
     def old_shard_len(self, r): return int(lib().ew_plan_old_shard_len(self.handle, r))
     def new_shard_len(self, r): return int(lib().ew_plan_new_shard_len(self.handle, r))
@@ -175,7 +191,9 @@ class Plan:
     def holder_of(self, r): return int(lib().ew_plan_holder_of(self.handle, r))
     def pair_len(self, h, k): return int(lib().ew_plan_pair_len(self.handle, h, k))
     def pair_off(self, h, k): return int(lib().ew_plan_pair_off(self.handle, h, k))
-    def num_tiles(self, which): return int(lib().ew_plan_num_tiles(self.handle, which))
+    def num_tiles(self, which, elem_size): return int(lib().ew_plan_num_tiles(self.handle, which, elem_size))
+    @property
+    def num_runs(self): return int(lib().ew_plan_num_runs(self.handle))
 
 
 def ew_plan(old_dp, new_dp, alive_mask, numel, chunk) -> Plan:

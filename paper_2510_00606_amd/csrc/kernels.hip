@@ -17,12 +17,25 @@
 
 namespace {
 
-using ew::Tile;
+using ew::RunT;
+using ew::TileT;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kThreads = 256;  // 4 waves of 64
-constexpr int kUnroll = 4;     // 16-byte loads in flight per lane in the unrolled body
+#ifndef EW_THREADS
+#define EW_THREADS 256
+#endif
+#ifndef EW_UNROLL
+#define EW_UNROLL 4
+#endif
+#ifndef EW_NT_LOAD
+#define EW_NT_LOAD 1
+#endif
+#ifndef EW_NT_STORE
+#define EW_NT_STORE 1
+#endif
+constexpr int kThreads = EW_THREADS;  // waves of 64
+constexpr int kUnroll = EW_UNROLL;    // 16-byte loads in flight per lane in the unrolled body
 
 thread_local std::string g_hip_error = "no HIP error recorded";
 
@@ -37,10 +50,11 @@ int hip_fail(hipError_t e, const char *what) {
   } while (0)
 
 // process-wide launch-shape knobs (see ew_set_param)
-int64_t g_copy_wgs_per_cu = 8;     // persistent grid = CUs * this; 0 = one workgroup per tile
+int64_t g_copy_wgs_per_cu = 0;     // 0 = one workgroup per tile, else persistent grid = CUs * this
 int64_t g_cksum_sub_bytes = 65536; // bytes of a checksum block handled by one workgroup pass
 int64_t g_cksum_wgs_per_cu = 0;    // 0 = one workgroup per sub-block, else persistent grid
-int64_t g_default_tile_elems = 8192;
+int64_t g_tile_bytes = 4096;        // default copy tile: 256 lanes x one 128-bit vector
+int64_t g_tile_elems = 0;           // > 0 overrides tile_bytes with a size in elements
 
 int num_cus() {
   static int cached[64] = {0};
@@ -54,12 +68,29 @@ int num_cus() {
   return cached[dev];
 }
 
-__device__ __forceinline__ u32x4 load16(const u32x4 *p) { return __builtin_nontemporal_load(p); }
-__device__ __forceinline__ void store16(u32x4 *p, u32x4 v) { __builtin_nontemporal_store(v, p); }
+__device__ __forceinline__ u32x4 load16(const u32x4 *p) {
+#if EW_NT_LOAD
+  return __builtin_nontemporal_load(p);
+#else
+  return *p;
+#endif
+}
+__device__ __forceinline__ void store16(u32x4 *p, u32x4 v) {
+#if EW_NT_STORE
+  __builtin_nontemporal_store(v, p);
+#else
+  *p = v;
+#endif
+}
 
 // ------------------------------------------------------------------------------------------
-// Segment copy.  One workgroup handles one tile at a time; tiles never straddle a segment, so
-// a tile is a plain contiguous copy between two buffers picked from the pointer tables.
+// Segment copy.  One workgroup copies one tile: at most tile_elems elements of one segment of
+// one unit, i.e. a plain contiguous copy between two buffers picked from the pointer tables.
+// The tile id is decoded against the run-length tables: run (binary search over a handful of
+// records), unit inside the run (one division), tile template inside the unit.  Everything up
+// to the addresses is wave-uniform and runs on the scalar unit from scalar-cache-resident
+// tables, so no per-tile record is streamed from HBM.  The default tile is 4 KiB: every lane
+// moves one 128-bit vector, and the GPU is kept full by the sheer number of workgroups.
 // ------------------------------------------------------------------------------------------
 struct CopyTabs {
   const char *src[ew::kNumSrc];
@@ -67,10 +98,11 @@ struct CopyTabs {
 };
 
 template <int ES>
-__global__ __launch_bounds__(kThreads) void ew_segcopy_kernel(const Tile *__restrict__ tiles,
+__global__ __launch_bounds__(kThreads) void ew_segcopy_kernel(const RunT *__restrict__ runs, uint32_t nruns,
+                                                              const TileT *__restrict__ templ,
                                                               uint64_t ntiles, CopyTabs tabs) {
   for (uint64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
-    const Tile tl = tiles[t];
+    const ew::TileRef tl = ew::decode_tile(runs, nruns, templ, t);
     const char *s = tabs.src[tl.src_buf] + tl.src_off * ES;
     char *d = tabs.dst[tl.dst_buf] + tl.dst_off * ES;
     const uint32_t nbytes = tl.len * ES;
@@ -80,11 +112,11 @@ __global__ __launch_bounds__(kThreads) void ew_segcopy_kernel(const Tile *__rest
       const uint32_t nvec = nbytes >> 4;
       uint32_t i = threadIdx.x;
       for (; i + (kUnroll - 1) * kThreads < nvec; i += kUnroll * kThreads) {
-        u32x4 r[kUnroll];
+        u32x4 v[kUnroll];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) r[u] = load16(sv + i + u * kThreads);
+        for (int u = 0; u < kUnroll; ++u) v[u] = load16(sv + i + u * kThreads);
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) store16(dv + i + u * kThreads, r[u]);
+        for (int u = 0; u < kUnroll; ++u) store16(dv + i + u * kThreads, v[u]);
       }
       for (; i < nvec; i += kThreads) store16(dv + i, load16(sv + i));
       // fewer than 16 trailing bytes: whole elements, one per lane
@@ -280,45 +312,30 @@ __global__ __launch_bounds__(kCmpThreads) void ew_compare_kernel(const ew_cksum_
 // ------------------------------------------------------------------------------------------
 // launch helpers
 // ------------------------------------------------------------------------------------------
-int upload_tiles(const ew_plan_t &plan, int which, uint32_t tile_elems, ew::DeviceTiles &dt,
-                 hipStream_t stream) {
-  std::vector<Tile> tiles;
-  try {
-    ew::build_tiles(plan, which, tile_elems, tiles);
-  } catch (const std::bad_alloc &) {
-    return EW_ENOMEM;
-  }
-  dt.count = tiles.size();
-  if (tiles.empty()) return EW_OK;
-  const size_t bytes = tiles.size() * sizeof(Tile);
-  if (hipHostMalloc((void **)&dt.host, bytes, hipHostMallocDefault) != hipSuccess) return EW_ENOMEM;
-  std::memcpy(dt.host, tiles.data(), bytes);
-  if (hipMalloc((void **)&dt.dev, bytes) != hipSuccess) return EW_ENOMEM;
-  EW_HIP(hipMemcpyAsync(dt.dev, dt.host, bytes, hipMemcpyHostToDevice, stream));
-  return EW_OK;
+void release_tables(ew_plan_t *plan) {
+  if (plan->dev_buf) (void)hipFree(plan->dev_buf);
+  if (plan->host_buf) (void)hipHostFree(plan->host_buf);
+  plan->dev_buf = plan->host_buf = nullptr;
+  plan->uploaded = false;
+  for (int w = 0; w < 2; ++w)
+    for (int e = 0; e < 2; ++e) plan->tables[w][e] = ew::TileTable();
 }
 
-void release_tiles(ew::DeviceTiles &dt) {
-  if (dt.dev) (void)hipFree(dt.dev);
-  if (dt.host) (void)hipHostFree(dt.host);
-  dt = ew::DeviceTiles();
-}
-
-int launch_segcopy(const ew::DeviceTiles &dt, const CopyTabs &tabs, uint32_t elem_size,
-                   hipStream_t stream) {
-  if (dt.count == 0) return EW_OK;
-  uint64_t grid = dt.count;
+int launch_segcopy(const ew::TileTable &tt, const CopyTabs &tabs, uint32_t elem_size, hipStream_t stream) {
+  if (tt.ntiles == 0) return EW_OK;
+  uint64_t grid = tt.ntiles;
   if (g_copy_wgs_per_cu > 0) {
     const uint64_t cap = (uint64_t)num_cus() * (uint64_t)g_copy_wgs_per_cu;
     if (grid > cap) grid = cap;
   }
   if (grid > 0x7fffffffull) grid = 0x7fffffffull;
+  const uint32_t nruns = (uint32_t)tt.runs.size();
   if (elem_size == 2)
-    hipLaunchKernelGGL(ew_segcopy_kernel<2>, dim3((uint32_t)grid), dim3(kThreads), 0, stream, dt.dev,
-                       dt.count, tabs);
+    hipLaunchKernelGGL(ew_segcopy_kernel<2>, dim3((uint32_t)grid), dim3(kThreads), 0, stream, tt.d_runs, nruns,
+                       tt.d_templ, tt.ntiles, tabs);
   else
-    hipLaunchKernelGGL(ew_segcopy_kernel<4>, dim3((uint32_t)grid), dim3(kThreads), 0, stream, dt.dev,
-                       dt.count, tabs);
+    hipLaunchKernelGGL(ew_segcopy_kernel<4>, dim3((uint32_t)grid), dim3(kThreads), 0, stream, tt.d_runs, nruns,
+                       tt.d_templ, tt.ntiles, tabs);
   EW_HIP(hipGetLastError());
   return EW_OK;
 }
@@ -380,55 +397,91 @@ extern "C" {
 
 void ew_plan_free(ew_plan_t *plan) {
   if (!plan) return;
-  release_tiles(plan->pack);
-  release_tiles(plan->unpack);
+  release_tables(plan);
   delete plan;
 }
 
-uint64_t ew_plan_num_tiles(const ew_plan_t *plan, int which) {
-  if (!plan || (which != 0 && which != 1)) return 0;
-  if (plan->tile_elems) return which == 0 ? plan->pack.count : plan->unpack.count;
-  return ew::count_tiles(*plan, which, (uint32_t)g_default_tile_elems);
+uint64_t ew_plan_num_tiles(const ew_plan_t *plan, int which, uint32_t elem_size) {
+  if (!plan || (which != 0 && which != 1) || (elem_size != 2 && elem_size != 4)) return 0;
+  const int e = elem_size == 4 ? 1 : 0;
+  if (plan->uploaded) return plan->tables[which][e].ntiles;
+  const uint32_t te = g_tile_elems > 0 ? (uint32_t)g_tile_elems : (uint32_t)(g_tile_bytes / elem_size);
+  return ew::count_tiles(*plan, which, te);
 }
 
 int ew_plan_upload(ew_plan_t *plan, uint32_t tile_elems, void *stream) {
   if (!plan) return EW_EINVAL;
-  if (tile_elems == 0) tile_elems = (uint32_t)g_default_tile_elems;
   if (tile_elems > (1u << 24)) return EW_EINVAL;
-  release_tiles(plan->pack);
-  release_tiles(plan->unpack);
-  plan->tile_elems = 0;
-  int dev = 0;
-  EW_HIP(hipGetDevice(&dev));
-  int rc = upload_tiles(*plan, 0, tile_elems, plan->pack, (hipStream_t)stream);
-  if (rc == EW_OK) rc = upload_tiles(*plan, 1, tile_elems, plan->unpack, (hipStream_t)stream);
-  if (rc != EW_OK) {
-    release_tiles(plan->pack);
-    release_tiles(plan->unpack);
-    return rc;
+  release_tables(plan);
+  if (tile_elems == 0 && g_tile_elems > 0) tile_elems = (uint32_t)g_tile_elems;
+  size_t bytes = 0;
+  try {
+    for (int e = 0; e < 2; ++e) {
+      const uint32_t es = e ? 4u : 2u;
+      plan->tile_elems[e] = tile_elems ? tile_elems : (uint32_t)(g_tile_bytes / es);
+      for (int w = 0; w < 2; ++w) {
+        ew::TileTable &tt = plan->tables[w][e];
+        ew::build_tile_table(*plan, w, plan->tile_elems[e], tt);
+        if (tt.ntiles > 0x7fffffffull) {  // tile ids are workgroup ids
+          release_tables(plan);
+          return EW_EINVAL;
+        }
+        bytes += tt.runs.size() * sizeof(RunT) + tt.templ.size() * sizeof(TileT);
+      }
+    }
+  } catch (const std::bad_alloc &) {
+    release_tables(plan);
+    return EW_ENOMEM;
   }
-  plan->device = dev;
-  plan->tile_elems = tile_elems;
+  if (bytes > 0) {
+    if (hipHostMalloc(&plan->host_buf, bytes, hipHostMallocDefault) != hipSuccess ||
+        hipMalloc(&plan->dev_buf, bytes) != hipSuccess) {
+      release_tables(plan);
+      return EW_ENOMEM;
+    }
+    size_t off = 0;
+    char *h = (char *)plan->host_buf, *d = (char *)plan->dev_buf;
+    for (int w = 0; w < 2; ++w)
+      for (int e = 0; e < 2; ++e) {  // templates (48 B records) first keeps everything 16-byte aligned
+        ew::TileTable &tt = plan->tables[w][e];
+        const size_t tb = tt.templ.size() * sizeof(TileT), rb = tt.runs.size() * sizeof(RunT);
+        std::memcpy(h + off, tt.templ.data(), tb);
+        tt.d_templ = (const TileT *)(d + off);
+        off += tb;
+        std::memcpy(h + off, tt.runs.data(), rb);
+        tt.d_runs = (const RunT *)(d + off);
+        off += rb;
+      }
+    const hipError_t e = hipMemcpyAsync(plan->dev_buf, plan->host_buf, bytes, hipMemcpyHostToDevice,
+                                        (hipStream_t)stream);
+    if (e != hipSuccess) {
+      release_tables(plan);
+      return hip_fail(e, "hipMemcpyAsync(tile tables)");
+    }
+  }
+  plan->uploaded = true;
   return EW_OK;
 }
 
 int ew_pack(const ew_plan_t *plan, const void *const *old_shards, const void *const *snapshots,
             void *stage, uint32_t elem_size, void *stream) {
-  if (!plan || plan->tile_elems == 0 || (elem_size != 2 && elem_size != 4)) return EW_EINVAL;
-  if (plan->pack.count == 0) return EW_OK;
+  if (!plan || !plan->uploaded || (elem_size != 2 && elem_size != 4)) return EW_EINVAL;
+  const ew::TileTable &tt = plan->tables[0][elem_size == 4 ? 1 : 0];
+  if (tt.ntiles == 0) return EW_OK;
   if (!stage) return EW_EINVAL;
   CopyTabs tabs;
   const int rc = fill_tabs(plan, old_shards, snapshots, tabs, false);
   if (rc != EW_OK) return rc;
   tabs.dst[ew::kDstStage] = (char *)stage;
-  return launch_segcopy(plan->pack, tabs, elem_size, (hipStream_t)stream);
+  return launch_segcopy(tt, tabs, elem_size, (hipStream_t)stream);
 }
 
 int ew_unpack(const ew_plan_t *plan, const void *stage, const void *const *old_shards,
               const void *const *snapshots, void *const *new_shards, uint32_t elem_size,
               void *stream) {
-  if (!plan || plan->tile_elems == 0 || (elem_size != 2 && elem_size != 4)) return EW_EINVAL;
-  if (plan->unpack.count == 0) return EW_OK;
+  if (!plan || !plan->uploaded || (elem_size != 2 && elem_size != 4)) return EW_EINVAL;
+  const ew::TileTable &tt = plan->tables[1][elem_size == 4 ? 1 : 0];
+  if (tt.ntiles == 0) return EW_OK;
   if (!new_shards) return EW_EINVAL;
   if (plan->stage_len > 0 && !stage) return EW_EINVAL;
   CopyTabs tabs;
@@ -439,7 +492,7 @@ int ew_unpack(const ew_plan_t *plan, const void *stage, const void *const *old_s
     if (plan->new_len[k] > 0 && !new_shards[k]) return EW_EINVAL;
     tabs.dst[k] = (char *)new_shards[k];
   }
-  return launch_segcopy(plan->unpack, tabs, elem_size, (hipStream_t)stream);
+  return launch_segcopy(tt, tabs, elem_size, (hipStream_t)stream);
 }
 
 int ew_snapshot(const void *src, void *dst, uint64_t nbytes, ew_cksum_t *cksums, void *stream) {
@@ -475,9 +528,12 @@ int ew_set_param(const char *name, int64_t value) {
   } else if (!std::strcmp(name, "cksum_wgs_per_cu")) {
     if (value < 0 || value > 64) return EW_EINVAL;
     g_cksum_wgs_per_cu = value;
+  } else if (!std::strcmp(name, "tile_bytes")) {
+    if (value < 256 || value > (1 << 24) || (value & 15)) return EW_EINVAL;
+    g_tile_bytes = value;
   } else if (!std::strcmp(name, "tile_elems")) {
-    if (value < 64 || value > (1 << 24)) return EW_EINVAL;
-    g_default_tile_elems = value;
+    if (value < 0 || value > (1 << 24)) return EW_EINVAL;
+    g_tile_elems = value;
   } else {
     return EW_EINVAL;
   }
@@ -489,7 +545,8 @@ int64_t ew_get_param(const char *name) {
   if (!std::strcmp(name, "copy_wgs_per_cu")) return g_copy_wgs_per_cu;
   if (!std::strcmp(name, "cksum_sub_bytes")) return g_cksum_sub_bytes;
   if (!std::strcmp(name, "cksum_wgs_per_cu")) return g_cksum_wgs_per_cu;
-  if (!std::strcmp(name, "tile_elems")) return g_default_tile_elems;
+  if (!std::strcmp(name, "tile_elems")) return g_tile_elems;
+  if (!std::strcmp(name, "tile_bytes")) return g_tile_bytes;
   return -1;
 }
 

@@ -1,12 +1,14 @@
 // Host planner: Live Remap steps 1 and 2 (Sec. 5.2) under the interleaved ZeRO assignment
 // (Sec. 6.3, Fig. 10b).  Integer arithmetic only, no GPU work.
 //
-// For every unit the old cuts (degree old_dp) and the new cuts (degree new_dp) are two sorted
+// For one unit the old cuts (degree old_dp) and the new cuts (degree new_dp) are two sorted
 // lists over the same element range; their common refinement, swept with two cursors, is the
 // element-exact content of the overlap matrix M_overlap for that unit.  A refined interval is
 // one segment: it lies in exactly one old piece (so it has one owner, one holder, one source
 // buffer) and in exactly one new piece (one destination).  Offsets inside shards are running
-// sums of piece lengths because a shard is the concatenation of its pieces in unit order.
+// sums of piece lengths because a shard is the concatenation of its pieces in unit order; for
+// a run of equal units they advance by the same amounts from unit to unit, which is what the
+// run-length form records.
 #include <algorithm>
 #include <cstring>
 #include <new>
@@ -25,111 +27,148 @@ inline void piece_bounds(uint64_t L, uint32_t D, uint64_t *b) {
   }
 }
 
-template <class UnitLen>
-int build(uint32_t old_dp, uint32_t new_dp, uint64_t alive_mask, uint64_t n_units, UnitLen unit_len,
-          ew_plan_t **out) {
-  if (!out || old_dp == 0 || new_dp == 0 || old_dp > EW_MAX_DP || new_dp > EW_MAX_DP) return EW_EINVAL;
-  if (old_dp < 64 && (alive_mask >> old_dp) != 0) return EW_EINVAL;
+struct Builder {
+  ew_plan_t *p;
+  std::vector<uint64_t> old_cur, new_cur, pair_cur, pair_unit;
 
-  // Step 1, integrity check: every failed rank's partition must exist in the snapshot kept by
-  // its ring predecessor (worker i backs up worker (i+1) mod n, Sec. 5.1).
-  auto alive = [&](uint32_t j) { return (alive_mask >> j) & 1u; };
-  if (alive_mask == 0) return EW_EUNRECOVERABLE;
-  ew_plan_t *p = new (std::nothrow) ew_plan_t();
-  if (!p) return EW_ENOMEM;
-  try {
-    p->old_dp = old_dp;
-    p->new_dp = new_dp;
-    p->alive_mask = alive_mask;
-    p->holder_of.assign(old_dp, -1);
-    p->new_rank_of.assign(old_dp, -1);
-    int32_t next_new = 0;
-    for (uint32_t j = 0; j < old_dp; ++j) {
-      if (alive(j)) {
-        p->holder_of[j] = (int32_t)j;
-        if ((uint32_t)next_new < new_dp) p->new_rank_of[j] = next_new++;
-      } else {
-        const uint32_t h = (j + old_dp - 1) % old_dp;
-        if (!alive(h)) {
-          delete p;
-          return EW_EUNRECOVERABLE;
-        }
-        p->holder_of[j] = (int32_t)h;
-      }
-    }
+  explicit Builder(ew_plan_t *plan) : p(plan) {
+    old_cur.assign(p->old_dp, 0);
+    new_cur.assign(p->new_dp, 0);
+    pair_cur.assign((size_t)p->old_dp * p->new_dp, 0);
+    pair_unit.assign((size_t)p->old_dp * p->new_dp, 0);
+  }
 
-    p->old_len.assign(old_dp, 0);
-    p->new_len.assign(new_dp, 0);
-    p->pair_len.assign((size_t)old_dp * new_dp, 0);
-    p->pair_off.assign((size_t)old_dp * new_dp, 0);
-
-    // Step 2: sweep the units.
+  // n consecutive units of L elements each
+  void add_run(uint64_t L, uint64_t n) {
+    if (L == 0 || n == 0) return;
+    const uint32_t Do = p->old_dp, Dn = p->new_dp;
     uint64_t ob[EW_MAX_DP + 1], nb[EW_MAX_DP + 1];
-    uint64_t numel = 0;
-    for (uint64_t u = 0; u < n_units; ++u) {
-      const uint64_t L = unit_len(u);
-      if (L == 0) continue;
-      piece_bounds(L, old_dp, ob);
-      piece_bounds(L, new_dp, nb);
-      uint32_t j = 0, k = 0;
-      while (j < old_dp && k < new_dp) {
-        const uint64_t lo = std::max(ob[j], nb[k]);
-        const uint64_t hi = std::min(ob[j + 1], nb[k + 1]);
-        if (lo < hi) {
-          ew_seg_t s;
-          std::memset(&s, 0, sizeof(s));
-          const uint32_t h = (uint32_t)p->holder_of[j];
-          s.src_owner = (uint16_t)j;
-          s.holder = (uint16_t)h;
-          s.dst_rank = (uint16_t)k;
-          s.len = hi - lo;
-          s.src_off = p->old_len[j] + (lo - ob[j]);
-          s.dst_off = p->new_len[k] + (lo - nb[k]);
-          s.flags = 0;
-          if (!alive(j)) {
-            s.flags |= EW_SEG_SNAPSHOT;
-            p->snap_read |= 1ull << j;
-          } else {
-            p->live_read |= 1ull << j;
-          }
-          if (p->new_rank_of[h] == (int32_t)k) {
-            s.flags |= EW_SEG_LOCAL;
-            s.stage_off = EW_NO_STAGE;
-          } else {
-            // offset inside the pair's message for now; the message base is added below
-            uint64_t &pl = p->pair_len[(size_t)h * new_dp + k];
-            s.stage_off = pl;
-            pl += s.len;
-          }
-          p->segs.push_back(s);
+    piece_bounds(L, Do, ob);
+    piece_bounds(L, Dn, nb);
+    ew::Run run;
+    run.n_units = n;
+    run.unit_len = L;
+    run.seg_begin = (uint32_t)p->run_segs.size();
+    std::fill(pair_unit.begin(), pair_unit.end(), 0);
+    uint32_t j = 0, k = 0;
+    while (j < Do && k < Dn) {
+      const uint64_t lo = std::max(ob[j], nb[k]);
+      const uint64_t hi = std::min(ob[j + 1], nb[k + 1]);
+      if (lo < hi) {
+        ew::RunSeg s;
+        std::memset(&s, 0, sizeof(s));
+        const bool owner_alive = (p->alive_mask >> j) & 1u;
+        const uint32_t h = (uint32_t)p->holder_of[j];
+        s.src_owner = (uint16_t)j;
+        s.holder = (uint16_t)h;
+        s.dst_rank = (uint16_t)k;
+        s.len = hi - lo;
+        s.src_off = old_cur[j] + (lo - ob[j]);
+        s.dst_off = new_cur[k] + (lo - nb[k]);
+        s.src_stride = ob[j + 1] - ob[j];
+        s.dst_stride = nb[k + 1] - nb[k];
+        if (!owner_alive) {
+          s.flags |= EW_SEG_SNAPSHOT;
+          p->snap_read |= 1ull << j;
+        } else {
+          p->live_read |= 1ull << j;
         }
-        const uint64_t oe = ob[j + 1], ne = nb[k + 1];
-        if (oe <= ne) ++j;
-        if (ne <= oe) ++k;
+        if (p->new_rank_of[h] == (int32_t)k) {
+          s.flags |= EW_SEG_LOCAL;
+          s.stage_off = EW_NO_STAGE;
+        } else {
+          // position inside the pair's message; the message base is added by finish()
+          const size_t idx = (size_t)h * Dn + k;
+          s.stage_off = pair_cur[idx] + pair_unit[idx];
+          pair_unit[idx] += s.len;
+        }
+        p->run_segs.push_back(s);
       }
-      for (uint32_t r = 0; r < old_dp; ++r) p->old_len[r] += ob[r + 1] - ob[r];
-      for (uint32_t r = 0; r < new_dp; ++r) p->new_len[r] += nb[r + 1] - nb[r];
-      numel += L;
+      const uint64_t oe = ob[j + 1], ne = nb[k + 1];
+      if (oe <= ne) ++j;
+      if (ne <= oe) ++k;
     }
-    p->numel = numel;
+    run.seg_end = (uint32_t)p->run_segs.size();
+    for (uint32_t i = run.seg_begin; i < run.seg_end; ++i) {
+      ew::RunSeg &s = p->run_segs[i];
+      if (!(s.flags & EW_SEG_LOCAL)) s.stage_stride = pair_unit[(size_t)s.holder * Dn + s.dst_rank];
+    }
+    for (uint32_t r = 0; r < Do; ++r) old_cur[r] += n * (ob[r + 1] - ob[r]);
+    for (uint32_t r = 0; r < Dn; ++r) new_cur[r] += n * (nb[r + 1] - nb[r]);
+    for (size_t i = 0; i < pair_cur.size(); ++i) pair_cur[i] += n * pair_unit[i];
+    p->numel += n * L;
+    p->num_segs += n * (uint64_t)(run.seg_end - run.seg_begin);
+    if (run.seg_end > run.seg_begin) p->runs.push_back(run);
+  }
 
-    // Arena: one contiguous message per (holder -> destination) pair, sorted by (dst, holder).
+  void finish() {
+    const uint32_t Do = p->old_dp, Dn = p->new_dp;
+    p->old_len = old_cur;
+    p->new_len = new_cur;
+    p->pair_len = pair_cur;
+    p->pair_off.assign((size_t)Do * Dn, 0);
+    // arena: one contiguous message per (holder -> destination) pair, sorted by (dst, holder)
     uint64_t off = 0;
-    for (uint32_t k = 0; k < new_dp; ++k)
-      for (uint32_t h = 0; h < old_dp; ++h) {
-        const size_t idx = (size_t)h * new_dp + k;
+    for (uint32_t k = 0; k < Dn; ++k)
+      for (uint32_t h = 0; h < Do; ++h) {
+        const size_t idx = (size_t)h * Dn + k;
         p->pair_off[idx] = off;
         off += p->pair_len[idx];
       }
     p->stage_len = off;
-    for (ew_seg_t &s : p->segs)
-      if (!(s.flags & EW_SEG_LOCAL)) s.stage_off += p->pair_off[(size_t)s.holder * new_dp + s.dst_rank];
-  } catch (const std::bad_alloc &) {
-    delete p;
-    return EW_ENOMEM;
+    for (ew::RunSeg &s : p->run_segs)
+      if (!(s.flags & EW_SEG_LOCAL)) s.stage_off += p->pair_off[(size_t)s.holder * Dn + s.dst_rank];
+  }
+};
+
+// Step 1, integrity check: every failed rank's partition must exist in the snapshot kept by its
+// ring predecessor (worker i backs up worker (i+1) mod n, Sec. 5.1).  Also fixes the new rank
+// numbering: survivors in order, densely from 0.
+int new_plan(uint32_t old_dp, uint32_t new_dp, uint64_t alive_mask, ew_plan_t **out) {
+  if (!out || old_dp == 0 || new_dp == 0 || old_dp > EW_MAX_DP || new_dp > EW_MAX_DP) return EW_EINVAL;
+  if (old_dp < 64 && (alive_mask >> old_dp) != 0) return EW_EINVAL;
+  if (alive_mask == 0) return EW_EUNRECOVERABLE;
+  auto alive = [&](uint32_t j) { return (alive_mask >> j) & 1u; };
+  for (uint32_t j = 0; j < old_dp; ++j)
+    if (!alive(j) && !alive((j + old_dp - 1) % old_dp)) return EW_EUNRECOVERABLE;
+  ew_plan_t *p = new (std::nothrow) ew_plan_t();
+  if (!p) return EW_ENOMEM;
+  p->old_dp = old_dp;
+  p->new_dp = new_dp;
+  p->alive_mask = alive_mask;
+  p->holder_of.assign(old_dp, -1);
+  p->new_rank_of.assign(old_dp, -1);
+  int32_t next_new = 0;
+  for (uint32_t j = 0; j < old_dp; ++j) {
+    if (alive(j)) {
+      p->holder_of[j] = (int32_t)j;
+      if ((uint32_t)next_new < new_dp) p->new_rank_of[j] = next_new++;
+    } else {
+      p->holder_of[j] = (int32_t)((j + old_dp - 1) % old_dp);
+    }
   }
   *out = p;
   return EW_OK;
+}
+
+void expand_segs(ew_plan_t *p) {
+  p->segs.reserve(p->num_segs);
+  for (const ew::Run &run : p->runs)
+    for (uint64_t i = 0; i < run.n_units; ++i)
+      for (uint32_t r = run.seg_begin; r < run.seg_end; ++r) {
+        const ew::RunSeg &t = p->run_segs[r];
+        ew_seg_t s;
+        std::memset(&s, 0, sizeof(s));
+        s.src_off = t.src_off + i * t.src_stride;
+        s.dst_off = t.dst_off + i * t.dst_stride;
+        s.stage_off = (t.flags & EW_SEG_LOCAL) ? EW_NO_STAGE : t.stage_off + i * t.stage_stride;
+        s.len = t.len;
+        s.src_owner = t.src_owner;
+        s.holder = t.holder;
+        s.dst_rank = t.dst_rank;
+        s.flags = t.flags;
+        p->segs.push_back(s);
+      }
 }
 
 }  // namespace
@@ -138,46 +177,68 @@ namespace ew {
 
 uint64_t count_tiles(const ew_plan_t &plan, int which, uint32_t tile_elems) {
   uint64_t n = 0;
-  for (const ew_seg_t &s : plan.segs) {
-    if (which == 0 && (s.flags & EW_SEG_LOCAL)) continue;
-    n += (s.len + tile_elems - 1) / tile_elems;
+  for (const Run &run : plan.runs) {
+    uint64_t per_unit = 0;
+    for (uint32_t r = run.seg_begin; r < run.seg_end; ++r) {
+      const RunSeg &s = plan.run_segs[r];
+      if (which == 0 && (s.flags & EW_SEG_LOCAL)) continue;
+      per_unit += (s.len + tile_elems - 1) / tile_elems;
+    }
+    n += per_unit * run.n_units;
   }
   return n;
 }
 
-void build_tiles(const ew_plan_t &plan, int which, uint32_t tile_elems, std::vector<Tile> &out) {
-  out.clear();
-  out.reserve(count_tiles(plan, which, tile_elems));
-  for (const ew_seg_t &s : plan.segs) {
-    const bool local = (s.flags & EW_SEG_LOCAL) != 0;
-    if (which == 0 && local) continue;
-    const uint16_t data_buf =
-        (uint16_t)((s.flags & EW_SEG_SNAPSHOT) ? kSrcSnap + s.src_owner : kSrcLive + s.holder);
-    Tile t;
-    std::memset(&t, 0, sizeof(t));
-    uint64_t src, dst;
-    if (which == 0) {  // source buffer -> arena
-      t.src_buf = data_buf;
-      t.dst_buf = (uint16_t)kDstStage;
-      src = s.src_off;
-      dst = s.stage_off;
-    } else if (local) {  // source buffer -> new shard
-      t.src_buf = data_buf;
-      t.dst_buf = s.dst_rank;
-      src = s.src_off;
-      dst = s.dst_off;
-    } else {  // arena -> new shard
-      t.src_buf = (uint16_t)kSrcStage;
-      t.dst_buf = s.dst_rank;
-      src = s.stage_off;
-      dst = s.dst_off;
+void build_tile_table(const ew_plan_t &plan, int which, uint32_t tile_elems, TileTable &out) {
+  out.runs.clear();
+  out.templ.clear();
+  out.ntiles = 0;
+  for (const Run &run : plan.runs) {
+    RunT rt;
+    rt.tile_begin = out.ntiles;
+    rt.templ_begin = (uint32_t)out.templ.size();
+    for (uint32_t r = run.seg_begin; r < run.seg_end; ++r) {
+      const RunSeg &s = plan.run_segs[r];
+      const bool local = (s.flags & EW_SEG_LOCAL) != 0;
+      if (which == 0 && local) continue;
+      const uint16_t data_buf =
+          (uint16_t)((s.flags & EW_SEG_SNAPSHOT) ? kSrcSnap + s.src_owner : kSrcLive + s.holder);
+      TileT t;
+      std::memset(&t, 0, sizeof(t));
+      uint64_t src, dst;
+      if (which == 0) {  // source buffer -> arena
+        t.src_buf = data_buf;
+        t.dst_buf = (uint16_t)kDstStage;
+        src = s.src_off;
+        dst = s.stage_off;
+        t.src_stride = s.src_stride;
+        t.dst_stride = s.stage_stride;
+      } else if (local) {  // source buffer -> new shard
+        t.src_buf = data_buf;
+        t.dst_buf = s.dst_rank;
+        src = s.src_off;
+        dst = s.dst_off;
+        t.src_stride = s.src_stride;
+        t.dst_stride = s.dst_stride;
+      } else {  // arena -> new shard
+        t.src_buf = (uint16_t)kSrcStage;
+        t.dst_buf = s.dst_rank;
+        src = s.stage_off;
+        dst = s.dst_off;
+        t.src_stride = s.stage_stride;
+        t.dst_stride = s.dst_stride;
+      }
+      for (uint64_t done = 0; done < s.len; done += tile_elems) {
+        t.src_off = src + done;
+        t.dst_off = dst + done;
+        t.len = (uint32_t)std::min<uint64_t>(tile_elems, s.len - done);
+        out.templ.push_back(t);
+      }
     }
-    for (uint64_t done = 0; done < s.len; done += tile_elems) {
-      t.src_off = src + done;
-      t.dst_off = dst + done;
-      t.len = (uint32_t)std::min<uint64_t>(tile_elems, s.len - done);
-      out.push_back(t);
-    }
+    rt.tiles_per_unit = (uint32_t)(out.templ.size() - rt.templ_begin);
+    if (rt.tiles_per_unit == 0) continue;
+    out.runs.push_back(rt);
+    out.ntiles += (uint64_t)rt.tiles_per_unit * run.n_units;
   }
 }
 
@@ -188,9 +249,20 @@ extern "C" {
 int ew_plan(uint32_t old_dp, uint32_t new_dp, uint64_t alive_mask, uint64_t numel, uint64_t chunk,
             ew_plan_t **out) {
   if (chunk == 0) return EW_EINVAL;
-  const uint64_t n_units = numel / chunk + (numel % chunk ? 1 : 0);
-  return build(old_dp, new_dp, alive_mask, n_units,
-               [=](uint64_t u) { return std::min(chunk, numel - u * chunk); }, out);
+  ew_plan_t *p = nullptr;
+  const int rc = new_plan(old_dp, new_dp, alive_mask, &p);
+  if (rc != EW_OK) return rc;
+  try {
+    Builder b(p);
+    b.add_run(chunk, numel / chunk);
+    b.add_run(numel % chunk, 1);
+    b.finish();
+  } catch (const std::bad_alloc &) {
+    delete p;
+    return EW_ENOMEM;
+  }
+  *out = p;
+  return EW_OK;
 }
 
 int ew_plan_bounds(uint32_t old_dp, uint32_t new_dp, uint64_t alive_mask, uint64_t n_units,
@@ -198,15 +270,68 @@ int ew_plan_bounds(uint32_t old_dp, uint32_t new_dp, uint64_t alive_mask, uint64
   if (!unit_starts || unit_starts[0] != 0) return EW_EINVAL;
   for (uint64_t u = 0; u < n_units; ++u)
     if (unit_starts[u + 1] < unit_starts[u]) return EW_EINVAL;
-  return build(old_dp, new_dp, alive_mask, n_units,
-               [=](uint64_t u) { return unit_starts[u + 1] - unit_starts[u]; }, out);
+  ew_plan_t *p = nullptr;
+  const int rc = new_plan(old_dp, new_dp, alive_mask, &p);
+  if (rc != EW_OK) return rc;
+  try {
+    Builder b(p);
+    uint64_t u = 0;
+    while (u < n_units) {  // runs of equal-length units
+      const uint64_t L = unit_starts[u + 1] - unit_starts[u];
+      uint64_t v = u + 1;
+      while (v < n_units && unit_starts[v + 1] - unit_starts[v] == L) ++v;
+      b.add_run(L, v - u);
+      u = v;
+    }
+    b.finish();
+  } catch (const std::bad_alloc &) {
+    delete p;
+    return EW_ENOMEM;
+  }
+  *out = p;
+  return EW_OK;
+}
+
+int ew_plan_tiles(const ew_plan_t *p, int which, uint32_t tile_elems, uint64_t first, uint64_t count,
+                  ew_tile_t *out, uint64_t *total) {
+  if (!p || (which != 0 && which != 1) || tile_elems == 0 || tile_elems > (1u << 24)) return EW_EINVAL;
+  if (count > 0 && !out) return EW_EINVAL;
+  try {
+    ew::TileTable tt;
+    ew::build_tile_table(*p, which, tile_elems, tt);
+    if (total) *total = tt.ntiles;
+    if (count == 0) return EW_OK;
+    if (first > tt.ntiles || count > tt.ntiles - first) return EW_EINVAL;
+    for (uint64_t i = 0; i < count; ++i) {
+      const ew::TileRef r =
+          ew::decode_tile(tt.runs.data(), (uint32_t)tt.runs.size(), tt.templ.data(), first + i);
+      out[i].src_off = r.src_off;
+      out[i].dst_off = r.dst_off;
+      out[i].len = r.len;
+      out[i].src_buf = r.src_buf;
+      out[i].dst_buf = r.dst_buf;
+    }
+  } catch (const std::bad_alloc &) {
+    return EW_ENOMEM;
+  }
+  return EW_OK;
 }
 
 uint64_t ew_plan_numel(const ew_plan_t *p) { return p ? p->numel : 0; }
 uint32_t ew_plan_old_dp(const ew_plan_t *p) { return p ? p->old_dp : 0; }
 uint32_t ew_plan_new_dp(const ew_plan_t *p) { return p ? p->new_dp : 0; }
-uint64_t ew_plan_num_segs(const ew_plan_t *p) { return p ? p->segs.size() : 0; }
-const ew_seg_t *ew_plan_segs(const ew_plan_t *p) { return p ? p->segs.data() : nullptr; }
+uint64_t ew_plan_num_segs(const ew_plan_t *p) { return p ? p->num_segs : 0; }
+uint64_t ew_plan_num_runs(const ew_plan_t *p) { return p ? p->runs.size() : 0; }
+const ew_seg_t *ew_plan_segs(const ew_plan_t *cp) {
+  if (!cp) return nullptr;
+  ew_plan_t *p = const_cast<ew_plan_t *>(cp);  // the cache is the only mutable part
+  try {
+    std::call_once(p->segs_once, expand_segs, p);
+  } catch (const std::bad_alloc &) {
+    return nullptr;
+  }
+  return p->segs.data();
+}
 uint64_t ew_plan_old_shard_len(const ew_plan_t *p, uint32_t r) {
   return (p && r < p->old_dp) ? p->old_len[r] : 0;
 }

@@ -1,26 +1,54 @@
 // Internal layout of the plan object shared by the host planner and the launch code.
+//
+// The plan is kept in run-length form: consecutive units (the paper's layers) of equal length
+// split identically, so a run of n such units is stored as ONE unit's segments plus, for each
+// segment, the distance its source / destination / arena offsets advance from one unit to the
+// next.  A uniform interleave chunk gives two runs (the full units and the short last one)
+// whatever the state size, so planning and the table upload cost microseconds, not a pass over
+// 10^5 segments.  The explicit segment table of the C ABI is expanded from it on demand.
 #pragma once
 
 #include <cstdint>
+#include <mutex>
 #include <vector>
 
 #include "elaswave.h"
 
 namespace ew {
 
-// One unit of copy work for a workgroup: at most tile_elems elements of one segment.
-// src_buf indexes the source pointer table (kSrcLive + old rank, kSrcSnap + owner, kSrcStage),
-// dst_buf the destination table (new rank, or kDstStage).  32 bytes so that one record is a
-// single aligned scalar load.
-struct Tile {
-  uint64_t src_off;  // elements
-  uint64_t dst_off;  // elements
-  uint32_t len;      // elements, 1..tile_elems
-  uint16_t src_buf;
-  uint16_t dst_buf;
+// A segment of the first unit of a run, with per-unit strides (all in elements).
+struct RunSeg {
+  uint64_t src_off, dst_off, stage_off, len;
+  uint64_t src_stride, dst_stride, stage_stride;
+  uint16_t src_owner, holder, dst_rank, flags;
+};
+
+struct Run {
+  uint64_t n_units;   // consecutive units of this length
+  uint64_t unit_len;  // elements
+  uint32_t seg_begin, seg_end;  // range in ew_plan_s::run_segs
+};
+
+// ---- device tables ------------------------------------------------------------------------
+// One unit of copy work for a workgroup: at most tile_elems elements of one segment of one
+// unit.  A tile template belongs to a run; for unit i of the run the offsets are
+// off0 + i * stride.  src_buf indexes the source pointer table (kSrcLive + old rank,
+// kSrcSnap + owner, kSrcStage), dst_buf the destination table (new rank, or kDstStage).
+struct TileT {
+  uint64_t src_off, dst_off;        // elements, unit 0 of the run
+  uint64_t src_stride, dst_stride;  // elements per unit
+  uint32_t len;                     // elements, 1..tile_elems
+  uint16_t src_buf, dst_buf;
   uint64_t pad;
 };
-static_assert(sizeof(Tile) == 32, "tile record must stay 32 bytes");
+static_assert(sizeof(TileT) == 48, "tile template must stay 48 bytes");
+
+struct RunT {
+  uint64_t tile_begin;      // global id of the run's first tile
+  uint32_t tiles_per_unit;  // templates per unit (> 0)
+  uint32_t templ_begin;     // index of the run's first template
+};
+static_assert(sizeof(RunT) == 16, "run record must stay 16 bytes");
 
 constexpr uint32_t kSrcLive = 0;
 constexpr uint32_t kSrcSnap = EW_MAX_DP;
@@ -29,10 +57,48 @@ constexpr uint32_t kNumSrc = 2 * EW_MAX_DP + 1;
 constexpr uint32_t kDstStage = EW_MAX_DP;
 constexpr uint32_t kNumDst = EW_MAX_DP + 1;
 
-struct DeviceTiles {
-  Tile *host = nullptr;  // pinned staging copy, kept until the plan is freed
-  Tile *dev = nullptr;
-  uint64_t count = 0;
+// Tile id -> (buffers, offsets, length).  The one decoder, used by the copy kernel (where every
+// operand is wave-uniform and lives in scalar registers) and by the host-side ew_plan_tiles.
+struct TileRef {
+  uint64_t src_off, dst_off;  // elements
+  uint32_t len;
+  uint16_t src_buf, dst_buf;
+};
+
+#if defined(__HIPCC__)
+#define EW_HD __host__ __device__ inline __attribute__((always_inline))
+#else
+#define EW_HD inline
+#endif
+EW_HD TileRef decode_tile(const RunT *runs, uint32_t nruns, const TileT *templ, uint64_t t) {
+  uint32_t lo = 0, hi = nruns - 1;
+  while (lo < hi) {  // last run whose first tile is <= t
+    const uint32_t mid = (lo + hi + 1) >> 1;
+    if (runs[mid].tile_begin <= t)
+      lo = mid;
+    else
+      hi = mid - 1;
+  }
+  const RunT run = runs[lo];
+  const uint64_t local = t - run.tile_begin;
+  const uint64_t unit = local / run.tiles_per_unit;
+  const TileT tl = templ[run.templ_begin + (uint32_t)(local - unit * run.tiles_per_unit)];
+  TileRef r;
+  r.src_off = tl.src_off + unit * tl.src_stride;
+  r.dst_off = tl.dst_off + unit * tl.dst_stride;
+  r.len = tl.len;
+  r.src_buf = tl.src_buf;
+  r.dst_buf = tl.dst_buf;
+  return r;
+}
+
+struct TileTable {       // host-side description of one (which, elem size) table
+  std::vector<RunT> runs;
+  std::vector<TileT> templ;
+  uint64_t ntiles = 0;
+  // device addresses inside the plan's single device buffer
+  const RunT *d_runs = nullptr;
+  const TileT *d_templ = nullptr;
 };
 
 }  // namespace ew
@@ -41,21 +107,28 @@ struct ew_plan_s {
   uint32_t old_dp = 0, new_dp = 0;
   uint64_t alive_mask = 0;
   uint64_t numel = 0;
-  std::vector<uint64_t> old_len, new_len;      // shard lengths in elements
-  std::vector<int32_t> new_rank_of, holder_of; // per old rank
-  std::vector<ew_seg_t> segs;
-  std::vector<uint64_t> pair_len, pair_off;    // [holder * new_dp + dst_rank]
+  uint64_t num_segs = 0;
+  std::vector<uint64_t> old_len, new_len;       // shard lengths in elements
+  std::vector<int32_t> new_rank_of, holder_of;  // per old rank
+  std::vector<uint64_t> pair_len, pair_off;     // [holder * new_dp + dst_rank]
   uint64_t stage_len = 0;
-  uint64_t live_read = 0, snap_read = 0;       // bit j: some segment reads that buffer
+  uint64_t live_read = 0, snap_read = 0;        // bit j: some segment reads that buffer
+  std::vector<ew::Run> runs;
+  std::vector<ew::RunSeg> run_segs;
+  // explicit table, expanded on first request
+  std::once_flag segs_once;
+  std::vector<ew_seg_t> segs;
   // device side (filled by ew_plan_upload)
-  int device = -1;
-  uint32_t tile_elems = 0;
-  ew::DeviceTiles pack, unpack;
+  bool uploaded = false;
+  uint32_t tile_elems[2] = {0, 0};              // [0]: 2-byte elements, [1]: 4-byte elements
+  ew::TileTable tables[2][2];                   // [which: 0 pack, 1 unpack][elem size index]
+  void *host_buf = nullptr;                     // pinned staging copy, kept until the plan is freed
+  void *dev_buf = nullptr;
 };
 
 namespace ew {
-// Cuts the plan's segments into tiles.  which = 0: non-LOCAL segments, source -> arena.
-// which = 1: every segment, arena or local source -> new shard.
-void build_tiles(const ew_plan_t &plan, int which, uint32_t tile_elems, std::vector<Tile> &out);
+// Cuts the plan's run segments into tile templates.  which = 0: non-LOCAL segments, source ->
+// arena.  which = 1: every segment, arena or local source -> new shard.
+void build_tile_table(const ew_plan_t &plan, int which, uint32_t tile_elems, TileTable &out);
 uint64_t count_tiles(const ew_plan_t &plan, int which, uint32_t tile_elems);
 }  // namespace ew

@@ -16,7 +16,7 @@ MIB = 1 << 20
 
 @pytest.fixture(autouse=True)
 def default_params():
-    saved = {k: ew.ew_get_param(k) for k in ("tile_elems", "copy_wgs_per_cu", "cksum_sub_bytes", "cksum_wgs_per_cu")}
+    saved = {k: ew.ew_get_param(k) for k in ("tile_bytes", "tile_elems", "copy_wgs_per_cu", "cksum_sub_bytes", "cksum_wgs_per_cu")}
     yield
     for k, v in saved.items():
         ew.ew_set_param(k, v)
@@ -198,7 +198,7 @@ def test_reshard_medium(case, elem_size):
     reshard_case(*case, elem_size, rng)
 
 
-@pytest.mark.parametrize("tile_elems,wgs", [(64, 0), (1000, 1), (4096, 8), (8192, 0), (65536, 4), (1 << 20, 2)])
+@pytest.mark.parametrize("tile_elems,wgs", [(0, 0), (0, 2), (64, 0), (1000, 1), (4096, 8), (8192, 0), (65536, 4), (1 << 20, 2)])
 def test_reshard_launch_shapes(tile_elems, wgs):
     ew.ew_set_param("copy_wgs_per_cu", wgs)
     rng = np.random.default_rng(tile_elems)

@@ -233,3 +233,84 @@ def test_full_size_plans_are_consistent(name):
         assert (sel["src_off"][i].astype(np.int64) + (offs - sel["dst_off"][i].astype(np.int64)) == ooff).all()
     if name == "70b_stage":
         assert abs(p.stage_len / w.numel - 0.5) < 1e-4  # D -> D+1 closed form: half stays local
+
+
+# ------------------------------------------------------------------ copy tiles (host view of what the kernels decode)
+def expand(records):
+    """records: (src_buf, src_off, dst_buf, dst_off, len) -> per-element rows sorted by destination."""
+    rows = []
+    for sb, so, db, do, n in records:
+        i = np.arange(int(n), dtype=np.int64)
+        rows.append(np.stack([np.full_like(i, db), do + i, np.full_like(i, sb), so + i], axis=1))
+    if not rows:
+        return np.zeros((0, 4), np.int64)
+    a = np.concatenate(rows)
+    return a[np.lexsort((a[:, 1], a[:, 0]))]
+
+
+def seg_records(segs, which):
+    out = []
+    for s in segs:
+        local = bool(s["flags"] & ew.EW_SEG_LOCAL)
+        data = (64 + int(s["src_owner"])) if s["flags"] & ew.EW_SEG_SNAPSHOT else int(s["holder"])
+        if which == 0:
+            if not local:
+                out.append((data, int(s["src_off"]), 64, int(s["stage_off"]), int(s["len"])))
+        elif local:
+            out.append((data, int(s["src_off"]), int(s["dst_rank"]), int(s["dst_off"]), int(s["len"])))
+        else:
+            out.append((128, int(s["stage_off"]), int(s["dst_rank"]), int(s["dst_off"]), int(s["len"])))
+    return out
+
+
+def check_tiles(p, tile_elems):
+    segs = p.segs()
+    for which in (0, 1):
+        t = p.tiles(which, tile_elems)
+        assert (t["len"] > 0).all() and (t["len"] <= tile_elems).all()
+        got = expand([(int(x["src_buf"]), int(x["src_off"]), int(x["dst_buf"]), int(x["dst_off"]), int(x["len"]))
+                      for x in t])
+        want = expand(seg_records(segs, which))
+        assert got.shape == want.shape and (got == want).all()
+        if len(got):  # every destination element written exactly once
+            assert (np.diff(got[:, 0] * (1 << 40) + got[:, 1]) > 0).all()
+
+
+def test_tiles_cover_segments_exactly():
+    for (Do, Dn, mask, N, C) in [(4, 3, 0b1011, 8192, 512), (8, 7, 0xFF & ~(1 << 5), 30000 + 8 * 37, 2624),
+                                 (7, 8, 0x7F, 20000, 656), (6, 4, 0b111011, 9999, 107), (3, 3, 0b101, 5000, 500),
+                                 (5, 9, 0b10101, 8000, 8000), (2, 5, 0b01, 777, 8), (1, 1, 1, 100, 7), (4, 4, 0xF, 0, 8)]:
+        p = ew.ew_plan(Do, Dn, mask, N, C)
+        for te in (1, 7, 64, 100, 1024, 1 << 20):
+            check_tiles(p, te)
+    # explicit boundaries with many different unit lengths: many runs, some of them repeated
+    rng = np.random.default_rng(3)
+    lens = rng.choice([0, 8, 24, 100, 100, 100, 264, 264, 1000], size=60)
+    starts = np.concatenate([[0], np.cumsum(lens)]).astype(np.uint64)
+    p = ew.ew_plan_bounds(5, 3, 0b11011, starts)
+    assert 1 < p.num_runs <= 60
+    for te in (16, 100, 4096):
+        check_tiles(p, te)
+    assert p.num_tiles(0, 4) == len(p.tiles(0, 1024)) and p.num_tiles(1, 2) == len(p.tiles(1, 2048))
+
+
+def test_uniform_chunk_plans_are_two_runs():
+    w = configs.stage_7b()
+    p = ew.ew_plan(w.old_dp, w.new_dp, w.alive_mask, w.numel, w.chunk)
+    q = ew.ew_plan_bounds(w.old_dp, w.new_dp, w.alive_mask, w.unit_starts())
+    assert p.num_runs == q.num_runs == 2
+    assert p.segs().tobytes() == q.segs().tobytes()
+    # sampled tiles of the full-size table land inside the buffers they name
+    for which, es in ((0, 4), (1, 4), (1, 2)):
+        te = 4096 // es
+        total = p.num_tiles(which, es)
+        for first in (0, total // 2, total - 5):
+            out = np.zeros(5, ew.TILE_DTYPE)
+            rc = binding.lib().ew_plan_tiles(p.handle, which, te, first, 5, out.ctypes.data, None)
+            assert rc == 0
+            for x in out:
+                sb, db = int(x["src_buf"]), int(x["dst_buf"])
+                src_cap = p.stage_len if sb == 128 else p.old_shard_len(sb % 64)
+                dst_cap = p.stage_len if db == 64 else p.new_shard_len(db)
+                assert int(x["src_off"]) + int(x["len"]) <= src_cap
+                assert int(x["dst_off"]) + int(x["len"]) <= dst_cap
