@@ -34,7 +34,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="7b_stage", choices=["tiny", "7b_stage", "13b_stage"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-units", type=int, default=768)
+    ap.add_argument("--cpu-sample-units", type=int, default=8192)
     return ap.parse_args()
 
 
@@ -172,6 +172,22 @@ def main():
         p.close()
     assert int(n_bad.item()) == 0, "verification of an intact snapshot reported bad blocks"
 
+    # yardstick (outside the timed region): the library's plain copy kernel on one fp32 rank shard,
+    # i.e. what a copy with nothing else to do reaches on this GPU; these launches are also the
+    # known-size dispatches (ybytes read, ybytes written) that the profiler's byte counters are
+    # calibrated with
+    ysrc, ydst = old["W"][0], snap["W"][0]
+    ybytes = (old_len[0] * 4) & ~15
+    for _ in range(3):
+        ew.ew_memcpy(ysrc, ydst, ybytes, st)
+    y0, y1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    y0.record()
+    for _ in range(10):
+        ew.ew_memcpy(ysrc, ydst, ybytes, st)
+    y1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 2 * ybytes * 10 / y0.elapsed_time(y1) / 1e6
+
     ms_per_step = elapsed / args.steps * 1e3
     value = step_bytes / (elapsed / args.steps) / 1e9
     phase_ms = {ph: 0.0 for ph in phases}
@@ -214,6 +230,7 @@ def main():
         "plan_ms": round(plan_ms, 3),
         "step_GB": round(step_bytes / 1e9, 3),
         "kernels": kernels,
+        "plain_copy_GBps": round(copy_gbs, 1),
         "roofline": roofline,
     }
 

@@ -177,6 +177,13 @@ int ew_verify(const void *buf, uint64_t nbytes, const ew_cksum_t *expect, ew_cks
               uint64_t *n_bad, uint64_t *bad_blocks, ew_cksum_t *diffs, uint64_t cap,
               void *stream);
 
+/* Plain device copy dst[0..nbytes) = src[0..nbytes) with the access pattern of the copy tiles
+ * (128-bit vectors, 4 KiB per workgroup) and nothing else: the yardstick that benchmarks quote
+ * the other kernels against and that profiler byte counters are calibrated with.  Not part of
+ * the paper's method.  src, dst: device, 16-byte aligned, non-overlapping; nbytes a multiple of
+ * 16 and at most (2^31-1) * 4 KiB, else EW_EINVAL. */
+int ew_memcpy(const void *src, void *dst, uint64_t nbytes, void *stream);
+
 /* Launch-shape knobs for benchmarking sweeps (process-wide, not thread-safe; defaults are the
  * tuned ones).  Names: "tile_bytes", "tile_elems", "copy_wgs_per_cu", "cksum_sub_bytes",
  * "cksum_wgs_per_cu".

@@ -64,6 +64,7 @@ _SIGNATURES = {
     "ew_snapshot": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]),
     "ew_verify": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                             C.c_uint64, C.c_void_p]),
+    "ew_memcpy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]),
     "ew_set_param": (C.c_int, [C.c_char_p, C.c_int64]),
     "ew_get_param": (C.c_int64, [C.c_char_p]),
     "ew_strerror": (C.c_char_p, [C.c_int]),
@@ -271,6 +272,14 @@ def ew_verify(buf, nbytes: int, expect, got, n_bad, bad_blocks, diffs, cap: int,
             raise ValueError(f"{name} holds {n} bytes, call needs {need}")
     _check(lib().ew_verify(_ptr(buf), nbytes, _ptr(expect), _ptr(got), _ptr(n_bad), _ptr(bad_blocks), _ptr(diffs),
                            cap, _stream(stream)), "ew_verify")
+
+
+def ew_memcpy(src, dst, nbytes: int, stream=None):
+    for name, b in (("src", src), ("dst", dst)):
+        n = _nbytes(b)
+        if n is not None and n < nbytes:
+            raise ValueError(f"{name} holds {n} bytes, call needs {nbytes}")
+    _check(lib().ew_memcpy(_ptr(src), _ptr(dst), nbytes, _stream(stream)), "ew_memcpy")
 
 
 def ew_set_param(name: str, value: int):

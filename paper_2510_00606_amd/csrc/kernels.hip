@@ -260,6 +260,15 @@ __global__ __launch_bounds__(kThreads) void ew_cksum_kernel(const char *__restri
   }
 }
 
+// Plain copy, one 128-bit vector per lane and 4 KiB per workgroup like the tile copy, no table
+// and no fold: the reference a profiler's byte counters and the other kernels' rates are
+// calibrated against.
+__global__ __launch_bounds__(kThreads) void ew_copy_kernel(const u32x4 *__restrict__ src,
+                                                           u32x4 *__restrict__ dst, uint64_t nvec) {
+  const uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i < nvec) store16(dst + i, load16(src + i));
+}
+
 __global__ __launch_bounds__(kThreads) void ew_zero_kernel(uint64_t *p, uint64_t nwords) {
   const uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
   if (i < nwords) p[i] = 0;
@@ -513,6 +522,18 @@ int ew_verify(const void *buf, uint64_t nbytes, const ew_cksum_t *expect, ew_cks
   const uint64_t nblocks = (nbytes + EW_CKSUM_BLOCK - 1) / EW_CKSUM_BLOCK;
   hipLaunchKernelGGL(ew_compare_kernel, dim3(1), dim3(kCmpThreads), 0, (hipStream_t)stream, got, expect,
                      nblocks, n_bad, bad_blocks, diffs, cap);
+  EW_HIP(hipGetLastError());
+  return EW_OK;
+}
+
+int ew_memcpy(const void *src, void *dst, uint64_t nbytes, void *stream) {
+  if (nbytes == 0) return EW_OK;
+  if (!src || !dst || (nbytes & 15u) || (((uintptr_t)src | (uintptr_t)dst) & 15u)) return EW_EINVAL;
+  const uint64_t nvec = nbytes >> 4;
+  const uint64_t grid = (nvec + kThreads - 1) / kThreads;
+  if (grid > 0x7fffffffull) return EW_EINVAL;
+  hipLaunchKernelGGL(ew_copy_kernel, dim3((uint32_t)grid), dim3(kThreads), 0, (hipStream_t)stream,
+                     (const u32x4 *)src, (u32x4 *)dst, nvec);
   EW_HIP(hipGetLastError());
   return EW_OK;
 }

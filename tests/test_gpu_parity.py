@@ -222,3 +222,16 @@ def test_null_buffers_are_rejected():
     # failed rank's live shard may be NULL: it is never read
     ew.ew_pack(plan, [old[0], old[1], None, old[3]], [None, None, old[2], None], stage, 4, stream())
     torch.cuda.synchronize()
+
+
+def test_plain_copy_yardstick():
+    rng = np.random.default_rng(5)
+    for nbytes in (16, 4096, 4096 * 3 + 16, 5 * MIB + 160):
+        raw = rng.integers(0, 256, nbytes, dtype=np.uint8)
+        src = torch.from_numpy(raw).to(DEV)
+        dst = torch.full((nbytes + 64,), 0x5A, dtype=torch.uint8, device=DEV)
+        ew.ew_memcpy(src, dst, nbytes, stream())
+        torch.cuda.synchronize()
+        assert np.array_equal(dst[:nbytes].cpu().numpy(), raw) and bool((dst[nbytes:] == 0x5A).all())
+    with pytest.raises(ew.EwError):
+        ew.ew_memcpy(src, dst, 24, stream())
