@@ -209,7 +209,7 @@ def main():
     snap_launches = launches["snapshot_old"] + launches["snapshot_new"]
     achieved = snap_bytes / snap_ms / 1e6
     roofline = {
-        "kernel": "ew_cksum_kernel<copy> (ew_snapshot)", "bound": "hbm", "achieved": round(achieved, 1),
+        "kernel": "ew_cksum_slots_kernel<copy> (+ ew_fold_kernel) = ew_snapshot", "bound": "hbm", "achieved": round(achieved, 1),
         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
         "traffic": read_traffic(f"ew_snapshot/{w.name}"),
         "bytes_per_launch": round(snap_bytes / snap_launches), "avg_launch_us": round(snap_ms / snap_launches * 1e3, 2),

@@ -164,7 +164,12 @@ int ew_unpack(const ew_plan_t *plan, const void *stage, const void *const *old_s
  * dst[0..nbytes) = src[0..nbytes); cksums[b] = (wrapping u64 sum, XOR) of the little-endian
  * 64-bit words of bytes [b*2^20, min((b+1)*2^20, nbytes)), a trailing partial word being
  * zero-padded.  src, dst, cksums: device; cksums has ceil(nbytes / 2^20) records and is
- * overwritten.  src and dst must not overlap.  nbytes = 0 is a no-op. */
+ * overwritten.  src and dst must not overlap.  nbytes = 0 is a no-op.
+ * Never allocates: per-workgroup partial checksums go through a fixed scratch array inside the
+ * library (64 MiB per device), one region per stream for the first 4 streams that call
+ * ew_snapshot / ew_verify on a device; calls on further streams, and calls with buffers that are
+ * not 16-byte aligned, use a slower kernel that needs no scratch.  Calls may be issued from
+ * several host threads. */
 int ew_snapshot(const void *src, void *dst, uint64_t nbytes, ew_cksum_t *cksums, void *stream);
 
 /* ---- Integrity check of stored bytes (Live Remap step 1) ----------------------------------
@@ -186,7 +191,8 @@ int ew_memcpy(const void *src, void *dst, uint64_t nbytes, void *stream);
 
 /* Launch-shape knobs for benchmarking sweeps (process-wide, not thread-safe; defaults are the
  * tuned ones).  Names: "tile_bytes", "tile_elems", "copy_wgs_per_cu", "cksum_sub_bytes",
- * "cksum_wgs_per_cu".
+ * "cksum_wgs_per_cu", "cksum_mode" (-1 = default: slot kernel + fold for ew_snapshot, atomic kernel
+ * for ew_verify; 0 / 1 force the slot / atomic kernel for both).
  * Returns EW_EINVAL for an unknown name or an out-of-range value. */
 int ew_set_param(const char *name, int64_t value);
 int64_t ew_get_param(const char *name);

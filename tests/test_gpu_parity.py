@@ -16,7 +16,8 @@ MIB = 1 << 20
 
 @pytest.fixture(autouse=True)
 def default_params():
-    saved = {k: ew.ew_get_param(k) for k in ("tile_bytes", "tile_elems", "copy_wgs_per_cu", "cksum_sub_bytes", "cksum_wgs_per_cu")}
+    saved = {k: ew.ew_get_param(k) for k in ("tile_bytes", "tile_elems", "copy_wgs_per_cu", "cksum_sub_bytes", "cksum_wgs_per_cu",
+                                              "cksum_mode")}
     yield
     for k, v in saved.items():
         ew.ew_set_param(k, v)
@@ -53,6 +54,7 @@ def test_snapshot_matches_oracle(nbytes):
 
 @pytest.mark.parametrize("sub,wgs", [(4096, 0), (16384, 2), (65536, 0), (262144, 1), (MIB, 0), (MIB, 3)])
 def test_snapshot_launch_shapes(sub, wgs):
+    ew.ew_set_param("cksum_mode", 1)   # the scratch-free atomic kernel
     ew.ew_set_param("cksum_sub_bytes", sub)
     ew.ew_set_param("cksum_wgs_per_cu", wgs)
     for nbytes in (1, 4097, MIB - 8, 9 * MIB + 100000 + 3, 64 * MIB):
@@ -109,7 +111,9 @@ def verify_case(nbytes, flips, rng, cap=16):
     return o_bad, o_diffs
 
 
-def test_verify_clean_and_single_flip():
+@pytest.mark.parametrize("mode", [-1, 0, 1])
+def test_verify_clean_and_single_flip(mode):
+    ew.ew_set_param("cksum_mode", mode)
     rng = np.random.default_rng(42)
     nbytes = 21 * MIB + 4096 + 5
     bad, _ = verify_case(nbytes, [], rng)
@@ -235,3 +239,54 @@ def test_plain_copy_yardstick():
         assert np.array_equal(dst[:nbytes].cpu().numpy(), raw) and bool((dst[nbytes:] == 0x5A).all())
     with pytest.raises(ew.EwError):
         ew.ew_memcpy(src, dst, 24, stream())
+
+
+def test_snapshot_on_many_streams():
+    """The first streams get a scratch region each, later ones take the scratch-free kernel;
+    every result is the oracle's."""
+    rng = np.random.default_rng(77)
+    streams = [torch.cuda.Stream() for _ in range(6)]
+    nbytes = 5 * MIB + 4096 + 9
+    raw = [rng.integers(0, 256, nbytes, dtype=np.uint8) for _ in streams]
+    src = [torch.from_numpy(r).to(DEV) for r in raw]
+    dst = [torch.zeros(nbytes, dtype=torch.uint8, device=DEV) for _ in streams]
+    ck = [torch.zeros((ew.num_blocks(nbytes), 2), dtype=torch.int64, device=DEV) for _ in streams]
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for i, s in enumerate(streams):
+            ew.ew_snapshot(src[i], dst[i], nbytes, ck[i], s.cuda_stream)
+    torch.cuda.synchronize()
+    for i in range(len(streams)):
+        assert np.array_equal(dst[i].cpu().numpy(), raw[i])
+        assert np.array_equal(ck[i].cpu().numpy().view(np.uint64), checksum.block_checksums(raw[i]))
+
+
+@pytest.mark.timeout(600)
+def test_snapshot_longer_than_one_scratch_pass():
+    """9 GiB + ragged tail: three passes over the 4 GiB scratch region."""
+    nbytes = 9 * (1 << 30) + 3 * MIB + 4096 + 5
+    src = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(11)
+    v = src[: (nbytes // 8) * 8].view(torch.int64)
+    step = 1 << 27
+    for o in range(0, v.numel(), step):
+        n = min(step, v.numel() - o)
+        v[o:o + n] = torch.randint(-(1 << 62), 1 << 62, (n,), dtype=torch.int64, device=DEV, generator=g)
+    src[(nbytes // 8) * 8:] = 0xA7
+    dst = torch.zeros(nbytes, dtype=torch.uint8, device=DEV)
+    nb = ew.num_blocks(nbytes)
+    ck = torch.full((nb, 2), -1, dtype=torch.int64, device=DEV)
+    ew.ew_snapshot(src, dst, nbytes, ck, stream())
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    got = ck.cpu().numpy().view(np.uint64)
+    # oracle on sampled blocks incl. both sides of every pass boundary and the ragged last block
+    blocks = sorted({0, 1, 4095, 4096, 4097, 8191, 8192, 8193, nb - 2, nb - 1} | set(np.random.default_rng(1).integers(0, nb, 24).tolist()))
+    for b in blocks:
+        host = src[b * MIB:min((b + 1) * MIB, nbytes)].cpu().numpy()
+        assert np.array_equal(got[b], checksum.block_checksums(host)[0]), f"block {b}"
+    # every block: sum of the records equals torch's wrapping sum of all words
+    total = int(v.sum().item()) & ((1 << 64) - 1)
+    tail = int.from_bytes(bytes([0xA7] * (nbytes % 8)), "little")
+    assert (int(got[:, 0].sum(dtype=np.uint64)) & ((1 << 64) - 1)) == (total + tail) & ((1 << 64) - 1)
