@@ -6,9 +6,11 @@ One step = one pass over one DP group's state (all four arrays P/W/M/V resident 
   a2 snapshot  ew_snapshot of every old rank's partition (copy + per-MiB checksums)
   a3 verify    ew_verify of the snapshots that replace failed ranks
   a4 pack      ew_pack   (non-local segments -> staging arena)
-  a6 unpack    ew_unpack (arena + local segments -> new shards)
-  a7 snapshot  ew_snapshot of every new rank's partition
-`value` is the algorithmic bytes (read + written) of a2..a7 divided by the step's wall time.
+  a6+a7        ew_unpack_snapshot: arena + local segments -> new shards, their snapshot copies and
+               the checksums of the new shards, every element read once
+               (--unfused: ew_unpack, then ew_snapshot of every new rank's partition)
+`value` is the algorithmic bytes (read + written) of the kernels as run divided by the step's
+wall time; `ms_per_step` is the figure that shows what fusing a6 and a7 saves.
 
 Prints ONE JSON line.  --gpus above 1 is refused: this build is one GPU only.
 """
@@ -34,6 +36,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="7b_stage", choices=["tiny", "7b_stage", "13b_stage"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--unfused", action="store_true", help="run a6 (ew_unpack) and a7 (ew_snapshot) as separate passes")
     ap.add_argument("--cpu-sample-units", type=int, default=8192)
     return ap.parse_args()
 
@@ -103,15 +106,25 @@ def main():
 
     numel = w.numel
     n_remote = stage_len
+    ck_new = 16 * sum(int(t.shape[0]) for a in A for t in nsums[a])
     bytes_phase = {
         "snapshot_old": sum(2 * n * 14 for n in old_len) + 16 * sum(int(t.shape[0]) for a in A for t in sums[a]),
         "verify": sum(old_len[j] * 14 for j in w.failed),
         "pack": 2 * 14 * n_remote,
-        "unpack": 2 * 14 * numel,
-        "snapshot_new": sum(2 * n * 14 for n in new_len) + 16 * sum(int(t.shape[0]) for a in A for t in nsums[a]),
     }
-    launches = {"snapshot_old": 4 * w.old_dp, "verify": 4 * len(w.failed), "pack": 4, "unpack": 4,
-                "snapshot_new": 4 * w.new_dp}
+    launches = {"snapshot_old": 4 * w.old_dp, "verify": 4 * len(w.failed), "pack": 4}
+    if args.unfused:
+        bytes_phase["unpack"] = 2 * 14 * numel
+        bytes_phase["snapshot_new"] = sum(2 * n * 14 for n in new_len) + ck_new
+        launches.update({"unpack": 4, "snapshot_new": 4 * w.new_dp})
+    else:
+        bytes_phase["unpack_snapshot"] = 3 * 14 * numel + ck_new    # read once, written twice
+        launches["unpack_snapshot"] = 4
+    kernel_of = {"snapshot_old": "ew_cksum_slots_kernel<copy> (+ ew_fold_kernel) = ew_snapshot",
+                 "snapshot_new": "ew_cksum_slots_kernel<copy> (+ ew_fold_kernel) = ew_snapshot",
+                 "verify": "ew_cksum_kernel<read-only> (+ ew_compare_kernel) = ew_verify",
+                 "pack": "ew_segcopy_kernel = ew_pack", "unpack": "ew_segcopy_kernel = ew_unpack",
+                 "unpack_snapshot": "ew_unpack_snap_kernel (+ ew_fold_tiles_kernel) = ew_unpack_snapshot"}
     step_bytes = sum(bytes_phase.values())
     phases = list(bytes_phase)
 
@@ -140,12 +153,16 @@ def main():
         for a in A:                                                                    # a4
             ew.ew_pack(plan, old_after[a], snap_used[a], stage[a], es[a], st)
         mark()
-        for a in A:                                                                    # a6
-            ew.ew_unpack(plan, stage[a], old_after[a], snap_used[a], new[a], es[a], st)
-        mark()
-        for a in A:                                                                    # a7
-            for k in range(w.new_dp):
-                ew.ew_snapshot(new[a][k], nsnap[a][k], new_len[k] * es[a], nsums[a][k], st)
+        if args.unfused:
+            for a in A:                                                                # a6
+                ew.ew_unpack(plan, stage[a], old_after[a], snap_used[a], new[a], es[a], st)
+            mark()
+            for a in A:                                                                # a7
+                for k in range(w.new_dp):
+                    ew.ew_snapshot(new[a][k], nsnap[a][k], new_len[k] * es[a], nsums[a][k], st)
+        else:
+            for a in A:                                                                # a6 + a7
+                ew.ew_unpack_snapshot(plan, stage[a], old_after[a], snap_used[a], new[a], nsnap[a], nsums[a], es[a], st)
         mark()
         return plan, t_plan, ev
 
@@ -203,18 +220,24 @@ def main():
             gbs = bytes_phase[ph] / phase_ms[ph] / 1e6
             kernels[ph] = {"ms": round(phase_ms[ph], 4), "launches": launches[ph], "GB": round(bytes_phase[ph] / 1e9, 4),
                            "GB/s": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4)}
-    # dominant kernel by traffic and time: the snapshot copy+checksum kernel (a2 and a7 launches)
-    snap_bytes = bytes_phase["snapshot_old"] + bytes_phase["snapshot_new"]
-    snap_ms = phase_ms["snapshot_old"] + phase_ms["snapshot_new"]
-    snap_launches = launches["snapshot_old"] + launches["snapshot_new"]
-    achieved = snap_bytes / snap_ms / 1e6
+    # dominant kernel: the one whose launches take the most time in a step (a2 and a7 are the same
+    # kernel when run unfused)
+    groups = {}
+    for ph in phases:
+        g = groups.setdefault(kernel_of[ph], [0.0, 0.0, 0])
+        g[0] += phase_ms[ph]
+        g[1] += bytes_phase[ph]
+        g[2] += launches[ph]
+    dom = max(groups, key=lambda k: groups[k][0])
+    d_ms, d_bytes, d_launches = groups[dom]
+    achieved = d_bytes / d_ms / 1e6
     roofline = {
-        "kernel": "ew_cksum_slots_kernel<copy> (+ ew_fold_kernel) = ew_snapshot", "bound": "hbm", "achieved": round(achieved, 1),
+        "kernel": dom, "bound": "hbm", "achieved": round(achieved, 1),
         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-        "traffic": read_traffic(f"ew_snapshot/{w.name}"),
-        "bytes_per_launch": round(snap_bytes / snap_launches), "avg_launch_us": round(snap_ms / snap_launches * 1e3, 2),
+        "traffic": read_traffic(f"{dom.split()[-1]}/{w.name}"),
+        "bytes_per_launch": round(d_bytes / d_launches), "avg_launch_us": round(d_ms / d_launches * 1e3, 2),
     }
-    reshard_ms = plan_ms + phase_ms["pack"] + phase_ms["unpack"]
+    reshard_ms = plan_ms + phase_ms["pack"] + phase_ms["unpack" if args.unfused else "unpack_snapshot"]
 
     out = {
         "metric": "reshard+snapshot GB/s on one MI355X and % of HBM peak; time to reshard one stage",
@@ -225,6 +248,8 @@ def main():
                    "new_dp": w.new_dp, "failed": w.failed, "units": int(len(starts) - 1),
                    "remote_fraction": round(n_remote / numel, 4), "arrays": "bf16 P + fp32 W, M, V"},
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
+        "path": "unfused (ew_unpack, then ew_snapshot of the new shards)" if args.unfused
+                else "fused (ew_unpack_snapshot also writes the new shards' snapshots and checksums)",
         "reshard_one_stage_ms": round(reshard_ms, 3),
         "reshard_useful_GBps": round(14 * numel / reshard_ms / 1e6, 1),
         "plan_ms": round(plan_ms, 3),

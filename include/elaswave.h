@@ -129,10 +129,11 @@ typedef struct {
   uint16_t src_buf;
   uint16_t dst_buf;
 } ew_tile_t;
-/* Writes tiles [first, first+count) of the table for `which` (0 pack, 1 unpack) cut at
- * tile_elems elements into out[] (host) and the table's tile count into *total (may be NULL). */
-int ew_plan_tiles(const ew_plan_t *plan, int which, uint32_t tile_elems, uint64_t first, uint64_t count,
-                  ew_tile_t *out, uint64_t *total);
+/* Writes tiles [first, first+count) of the table for `which` (0 pack, 1 unpack), cut at
+ * tile_elems elements with cut points on multiples of align_elems in the destination (0: no
+ * alignment), into out[] (host) and the table's tile count into *total (may be NULL). */
+int ew_plan_tiles(const ew_plan_t *plan, int which, uint32_t tile_elems, uint32_t align_elems, uint64_t first,
+                  uint64_t count, ew_tile_t *out, uint64_t *total);
 
 /* Builds the copy-tile tables (segments cut into pieces of at most tile_elems elements;
  * 0 = library default, 4 KiB worth of elements) for both element sizes and uploads them to the
@@ -160,13 +161,26 @@ int ew_unpack(const ew_plan_t *plan, const void *stage, const void *const *old_s
               const void *const *snapshots, void *const *new_shards, uint32_t elem_size,
               void *stream);
 
+/* ---- Unpack fused with the fresh snapshot of the new layout ---------------------------------
+ * Same result as ew_unpack followed, for every new rank k, by ew_snapshot(new_shards[k],
+ * new_snapshots[k], new_len[k]*elem_size, new_cksums[k]) -- the snapshot that makes the next
+ * failure recoverable (ring placement, Sec. 5.1) and verifiable (abstract) -- but every element is
+ * read once: it is stored to the new shard and to its snapshot copy and folded into the checksum
+ * of the new shard's 1 MiB block it lands in.  new_snapshots, new_cksums: host arrays of new_dp
+ * device pointers (buffers of new_len[k]*elem_size bytes / ceil(that / 2^20) records, records
+ * overwritten).  Uses the library's scratch array like ew_snapshot: EW_ENOMEM if more than 4
+ * streams of a device already use it; EW_EINVAL if the plan was uploaded with tiles above 1 MiB. */
+int ew_unpack_snapshot(const ew_plan_t *plan, const void *stage, const void *const *old_shards,
+                       const void *const *snapshots, void *const *new_shards, void *const *new_snapshots,
+                       ew_cksum_t *const *new_cksums, uint32_t elem_size, void *stream);
+
 /* ---- Per-step snapshot (Sec. 5.1) with block checksums ------------------------------------
  * dst[0..nbytes) = src[0..nbytes); cksums[b] = (wrapping u64 sum, XOR) of the little-endian
  * 64-bit words of bytes [b*2^20, min((b+1)*2^20, nbytes)), a trailing partial word being
  * zero-padded.  src, dst, cksums: device; cksums has ceil(nbytes / 2^20) records and is
  * overwritten.  src and dst must not overlap.  nbytes = 0 is a no-op.
  * Never allocates: per-workgroup partial checksums go through a fixed scratch array inside the
- * library (64 MiB per device), one region per stream for the first 4 streams that call
+ * library (128 MiB per device), one region per stream for the first 4 streams that call
  * ew_snapshot / ew_verify on a device; calls on further streams, and calls with buffers that are
  * not 16-byte aligned, use a slower kernel that needs no scratch.  Calls may be issued from
  * several host threads. */
@@ -190,7 +204,7 @@ int ew_verify(const void *buf, uint64_t nbytes, const ew_cksum_t *expect, ew_cks
 int ew_memcpy(const void *src, void *dst, uint64_t nbytes, void *stream);
 
 /* Launch-shape knobs for benchmarking sweeps (process-wide, not thread-safe; defaults are the
- * tuned ones).  Names: "tile_bytes", "tile_elems", "copy_wgs_per_cu", "cksum_sub_bytes",
+ * tuned ones).  Names: "tile_bytes", "tile_elems", "tile_align_bytes", "copy_wgs_per_cu", "cksum_sub_bytes",
  * "cksum_wgs_per_cu", "cksum_mode" (-1 = default: slot kernel + fold for ew_snapshot, atomic kernel
  * for ew_verify; 0 / 1 force the slot / atomic kernel for both).
  * Returns EW_EINVAL for an unknown name or an out-of-range value. */

@@ -56,11 +56,13 @@ _SIGNATURES = {
     "ew_plan_remote_elems": (C.c_uint64, [C.c_void_p]),
     "ew_plan_num_tiles": (C.c_uint64, [C.c_void_p, C.c_int, C.c_uint32]),
     "ew_plan_num_runs": (C.c_uint64, [C.c_void_p]),
-    "ew_plan_tiles": (C.c_int, [C.c_void_p, C.c_int, C.c_uint32, C.c_uint64, C.c_uint64, C.c_void_p,
+    "ew_plan_tiles": (C.c_int, [C.c_void_p, C.c_int, C.c_uint32, C.c_uint32, C.c_uint64, C.c_uint64, C.c_void_p,
                                 C.POINTER(C.c_uint64)]),
     "ew_plan_upload": (C.c_int, [C.c_void_p, C.c_uint32, C.c_void_p]),
     "ew_pack": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p]),
     "ew_unpack": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p]),
+    "ew_unpack_snapshot": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_uint32, C.c_void_p]),
     "ew_snapshot": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]),
     "ew_verify": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                             C.c_uint64, C.c_void_p]),
@@ -176,14 +178,17 @@ class Plan:
         buf = (C.c_char * (n * SEG_DTYPE.itemsize)).from_address(addr)
         return np.frombuffer(buf, dtype=SEG_DTYPE).copy()
 
-    def tiles(self, which: int, tile_elems: int) -> np.ndarray:
-        """All copy tiles of the pack (0) / unpack (1) table, decoded on the host."""
+    def tiles(self, which: int, tile_elems: int, align_elems: int = 0, first: int = 0, count=None) -> np.ndarray:
+        """Copy tiles of the pack (0) / unpack (1) table, decoded on the host (all of them by default)."""
         total = C.c_uint64()
-        _check(lib().ew_plan_tiles(self.handle, which, tile_elems, 0, 0, None, C.byref(total)), "ew_plan_tiles")
-        out = np.zeros(total.value, TILE_DTYPE)
-        if total.value:
-            _check(lib().ew_plan_tiles(self.handle, which, tile_elems, 0, total.value, out.ctypes.data, None),
-                   "ew_plan_tiles")
+        _check(lib().ew_plan_tiles(self.handle, which, tile_elems, align_elems, 0, 0, None, C.byref(total)),
+               "ew_plan_tiles")
+        if count is None:
+            count = total.value - first
+        out = np.zeros(count, TILE_DTYPE)
+        if count:
+            _check(lib().ew_plan_tiles(self.handle, which, tile_elems, align_elems, first, count, out.ctypes.data,
+                                       None), "ew_plan_tiles")
         return out
 
     def old_shard_len(self, r): return int(lib().ew_plan_old_shard_len(self.handle, r))
@@ -249,6 +254,26 @@ def ew_unpack(plan: Plan, stage, old_shards, snapshots, new_shards, elem_size: i
     _check(lib().ew_unpack(plan.handle, _ptr(stage), _ptr_array(old_shards, plan.old_dp),
                            _ptr_array(snapshots, plan.old_dp), _ptr_array(new_shards, plan.new_dp),
                            elem_size, _stream(stream)), "ew_unpack")
+
+
+def ew_unpack_snapshot(plan: Plan, stage, old_shards, snapshots, new_shards, new_snapshots, new_cksums,
+                       elem_size: int, stream=None):
+    _check_sources(plan, old_shards, snapshots, elem_size)
+    n = _nbytes(stage)
+    if n is not None and n < plan.stage_len * elem_size:
+        raise ValueError(f"staging arena holds {n} bytes, plan needs {plan.stage_len * elem_size}")
+    for k in range(plan.new_dp):
+        need = plan.new_shard_len(k) * elem_size
+        for name, bufs, want in (("new shard", new_shards, need), ("new snapshot", new_snapshots, need),
+                                 ("new checksum array", new_cksums, 16 * num_blocks(need))):
+            n = _nbytes(bufs[k]) if bufs[k] is not None else None
+            if n is not None and n < want:
+                raise ValueError(f"{name} {k} holds {n} bytes, plan needs {want}")
+    D = plan.new_dp
+    _check(lib().ew_unpack_snapshot(plan.handle, _ptr(stage), _ptr_array(old_shards, plan.old_dp),
+                                    _ptr_array(snapshots, plan.old_dp), _ptr_array(new_shards, D),
+                                    _ptr_array(new_snapshots, D), _ptr_array(new_cksums, D), elem_size,
+                                    _stream(stream)), "ew_unpack_snapshot")
 
 
 def num_blocks(nbytes: int) -> int:

@@ -12,6 +12,7 @@
 #include <cstring>
 #include <mutex>
 #include <string>
+#include <type_traits>
 #include <vector>
 
 #include "plan_internal.h"
@@ -58,6 +59,7 @@ int64_t g_cksum_mode = -1;         // -1 = slot kernel + fold for snapshot, atom
                                    // 0 / 1 force the slot / atomic kernel for both
 int64_t g_tile_bytes = 4096;        // default copy tile: 256 lanes x one 128-bit vector
 int64_t g_tile_elems = 0;           // > 0 overrides tile_bytes with a size in elements
+int64_t g_tile_align_bytes = 128;   // tile cuts fall on multiples of this in the destination (0: off)
 
 int num_cus() {
   static int cached[64] = {0};
@@ -163,10 +165,31 @@ __device__ __forceinline__ void fold(u32x4 v, uint64_t &sum, uint64_t &xr) {
   xr ^= w0 ^ w1;
 }
 
-__device__ __forceinline__ uint64_t shfl_xor64(uint64_t v, int mask) {
-  const uint32_t lo = __shfl_xor((int)(uint32_t)v, mask, 64);
-  const uint32_t hi = __shfl_xor((int)(uint32_t)(v >> 32), mask, 64);
+// Wave-wide fold of (sum, xor) with DPP moves: four row_shr steps inside each row of 16 lanes,
+// then row_bcast:15 and row_bcast:31 carry the row totals across rows.  Lanes a move does not
+// reach receive 0, the identity of both operations.  The wave's total ends up in lane 63.
+// (Six cross-lane steps on the VALU; the LDS-crossbar shuffles they replace cost 15 % of a 4 KiB
+// workgroup's run time.)
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint64_t dpp_mov64(uint64_t v) {
+  const uint32_t lo = __builtin_amdgcn_update_dpp(0u, (uint32_t)v, CTRL, ROW_MASK, 0xf, false);
+  const uint32_t hi = __builtin_amdgcn_update_dpp(0u, (uint32_t)(v >> 32), CTRL, ROW_MASK, 0xf, false);
   return (uint64_t)lo | ((uint64_t)hi << 32);
+}
+constexpr int kWaveFoldLane = 63;
+__device__ __forceinline__ void wave_fold(uint64_t &sum, uint64_t &xr) {
+  sum += dpp_mov64<0x111, 0xf>(sum);  // row_shr:1
+  xr ^= dpp_mov64<0x111, 0xf>(xr);
+  sum += dpp_mov64<0x112, 0xf>(sum);  // row_shr:2
+  xr ^= dpp_mov64<0x112, 0xf>(xr);
+  sum += dpp_mov64<0x114, 0xf>(sum);  // row_shr:4
+  xr ^= dpp_mov64<0x114, 0xf>(xr);
+  sum += dpp_mov64<0x118, 0xf>(sum);  // row_shr:8
+  xr ^= dpp_mov64<0x118, 0xf>(xr);
+  sum += dpp_mov64<0x142, 0xa>(sum);  // row_bcast:15 into rows 1 and 3
+  xr ^= dpp_mov64<0x142, 0xa>(xr);
+  sum += dpp_mov64<0x143, 0xc>(sum);  // row_bcast:31 into rows 2 and 3
+  xr ^= dpp_mov64<0x143, 0xc>(xr);
 }
 
 template <bool COPY, bool ALIGNED>
@@ -232,13 +255,9 @@ __global__ __launch_bounds__(kThreads) void ew_cksum_kernel(const char *__restri
       }
     }
     // wave fold
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) {
-      sum += shfl_xor64(sum, m);
-      xr ^= shfl_xor64(xr, m);
-    }
+    wave_fold(sum, xr);
     const int wave = threadIdx.x >> 6;
-    if ((threadIdx.x & 63) == 0) {
+    if ((threadIdx.x & 63) == kWaveFoldLane) {
       lds_sum[wave] = sum;
       lds_xor[wave] = xr;
     }
@@ -296,13 +315,9 @@ __global__ __launch_bounds__(kThreads) void ew_cksum_slots_kernel(const u32x4 *_
     sum = w[0] + w[1];
     xr = w[0] ^ w[1];
   }
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) {
-    sum += shfl_xor64(sum, m);
-    xr ^= shfl_xor64(xr, m);
-  }
+  wave_fold(sum, xr);
   const int wave = threadIdx.x >> 6;
-  if ((threadIdx.x & 63) == 0) {
+  if ((threadIdx.x & 63) == kWaveFoldLane) {
     lds_sum[wave] = sum;
     lds_xor[wave] = xr;
   }
@@ -330,13 +345,9 @@ __global__ __launch_bounds__(kThreads) void ew_fold_kernel(const ew_cksum_t *__r
       xr ^= r.xr;
     }
   }
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) {
-    sum += shfl_xor64(sum, m);
-    xr ^= shfl_xor64(xr, m);
-  }
+  wave_fold(sum, xr);
   const int wave = threadIdx.x >> 6;
-  if ((threadIdx.x & 63) == 0) {
+  if ((threadIdx.x & 63) == kWaveFoldLane) {
     lds_sum[wave] = sum;
     lds_xor[wave] = xr;
   }
@@ -350,6 +361,170 @@ __global__ __launch_bounds__(kThreads) void ew_fold_kernel(const ew_cksum_t *__r
     }
     out[blockIdx.x] = r;
   }
+}
+
+// ------------------------------------------------------------------------------------------
+// Unpack fused with the snapshot of the new shards: every tile is loaded once and stored twice
+// (new shard and its snapshot copy), and its bytes are folded into the checksum of the 1 MiB
+// block of the NEW shard they land in, so the fresh snapshot of the new layout costs no second
+// read pass.  A block's words arrive from many tiles, possibly in pieces that are not word
+// aligned (ragged units); both sum and xor decompose over bytes, so an element at byte offset o
+// of its shard contributes  element << 8*(o mod 8)  to the record of block o >> 20.
+// Each workgroup writes its tile's (sum, xor) to the tile's slot; the rare tile that straddles a
+// block boundary adds its upper part to the next block's record directly.  ew_fold_tiles_kernel
+// then walks the slots in tile order and adds runs of equal (rank, block) to the records.
+// ------------------------------------------------------------------------------------------
+struct SnapTabs {
+  char *snap[EW_MAX_DP];        // snapshot buffer of each new rank
+  ew_cksum_t *rec[EW_MAX_DP];   // checksum records of each new rank
+  uint32_t nblk[EW_MAX_DP];     // records per rank
+};
+
+// Workgroup-wide fold; the total is valid in thread 0.  Each call needs LDS cells of its own.
+__device__ __forceinline__ void block_fold(uint64_t &sum, uint64_t &xr, uint64_t *lds_sum, uint64_t *lds_xor) {
+  wave_fold(sum, xr);
+  const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == kWaveFoldLane) {
+    lds_sum[wave] = sum;
+    lds_xor[wave] = xr;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    sum = 0;
+    xr = 0;
+#pragma unroll
+    for (int w = 0; w < kThreads / 64; ++w) {
+      sum += lds_sum[w];
+      xr ^= lds_xor[w];
+    }
+  }
+}
+
+template <int ES>
+__global__ __launch_bounds__(kThreads) void ew_unpack_snap_kernel(const RunT *__restrict__ runs, uint32_t nruns,
+                                                                  const TileT *__restrict__ templ,
+                                                                  uint64_t tile_base, CopyTabs tabs, SnapTabs st,
+                                                                  ew_cksum_t *__restrict__ slots) {
+  __shared__ uint64_t lds_sum[kThreads / 64], lds_xor[kThreads / 64];
+  __shared__ uint64_t lds_sum_hi[kThreads / 64], lds_xor_hi[kThreads / 64];
+  typedef typename std::conditional<ES == 2, uint16_t, uint32_t>::type elem_t;
+  const ew::TileRef tl = ew::decode_tile(runs, nruns, templ, tile_base + blockIdx.x);
+  const char *s = tabs.src[tl.src_buf] + tl.src_off * ES;
+  const uint64_t dbyte = tl.dst_off * ES;  // byte offset inside the new shard
+  char *d = tabs.dst[tl.dst_buf] + dbyte;
+  char *d2 = st.snap[tl.dst_buf] + dbyte;
+  const uint32_t nbytes = tl.len * ES;
+  const uint64_t boundary = ((dbyte >> 20) + 1) << 20;  // where the next checksum block starts
+  const bool straddle = dbyte + nbytes > boundary;      // wave-uniform, rare
+  uint64_t sum = 0, xr = 0, sum_hi = 0, xr_hi = 0;
+  if ((((uintptr_t)s | (uintptr_t)d | (uintptr_t)d2 | dbyte) & 15u) == 0) {
+    const u32x4 *sv = reinterpret_cast<const u32x4 *>(s);
+    u32x4 *dv = reinterpret_cast<u32x4 *>(d);
+    u32x4 *d2v = reinterpret_cast<u32x4 *>(d2);
+    const uint32_t nvec = nbytes >> 4;
+    for (uint32_t i = threadIdx.x; i < nvec; i += kThreads) {  // one trip for the default 4 KiB tile
+      const u32x4 v = load16(sv + i);
+      store16(dv + i, v);
+      store16(d2v + i, v);
+      if (straddle && dbyte + 16ull * i >= boundary)
+        fold(v, sum_hi, xr_hi);
+      else
+        fold(v, sum, xr);
+    }
+    const uint32_t done = nvec << 4;
+    const uint32_t rem = (nbytes - done) / ES;  // fewer than 16 trailing bytes: whole elements
+    if (threadIdx.x < rem) {
+      const elem_t e = reinterpret_cast<const elem_t *>(s + done)[threadIdx.x];
+      reinterpret_cast<elem_t *>(d + done)[threadIdx.x] = e;
+      reinterpret_cast<elem_t *>(d2 + done)[threadIdx.x] = e;
+      const uint64_t o = dbyte + done + (uint64_t)threadIdx.x * ES;
+      const uint64_t c = (uint64_t)e << (8 * (o & 7));
+      if (o >= boundary) {
+        sum_hi += c;
+        xr_hi ^= c;
+      } else {
+        sum += c;
+        xr ^= c;
+      }
+    }
+  } else {
+    const elem_t *se = reinterpret_cast<const elem_t *>(s);
+    elem_t *de = reinterpret_cast<elem_t *>(d);
+    elem_t *d2e = reinterpret_cast<elem_t *>(d2);
+    for (uint32_t i = threadIdx.x; i < tl.len; i += kThreads) {
+      const elem_t e = se[i];
+      de[i] = e;
+      d2e[i] = e;
+      const uint64_t o = dbyte + (uint64_t)i * ES;
+      const uint64_t c = (uint64_t)e << (8 * (o & 7));
+      if (o >= boundary) {
+        sum_hi += c;
+        xr_hi ^= c;
+      } else {
+        sum += c;
+        xr ^= c;
+      }
+    }
+  }
+  block_fold(sum, xr, lds_sum, lds_xor);
+  if (threadIdx.x == 0) {
+    ew_cksum_t r;
+    r.sum = sum;
+    r.xr = xr;
+    slots[blockIdx.x] = r;
+  }
+  if (straddle) {
+    block_fold(sum_hi, xr_hi, lds_sum_hi, lds_xor_hi);
+    if (threadIdx.x == 0) {
+      ew_cksum_t *rec = st.rec[tl.dst_buf] + (boundary >> 20);
+      atomicAdd(reinterpret_cast<unsigned long long *>(&rec->sum), (unsigned long long)sum_hi);
+      atomicXor(reinterpret_cast<unsigned long long *>(&rec->xr), (unsigned long long)xr_hi);
+    }
+  }
+}
+
+// Lane g adds the slots of tiles [g*per_lane, (g+1)*per_lane) of the pass to the records, one
+// pair of atomics per run of tiles that share (new rank, block): tiles of a segment are adjacent.
+template <int ES>
+__global__ __launch_bounds__(kThreads) void ew_fold_tiles_kernel(const RunT *__restrict__ runs, uint32_t nruns,
+                                                                 const TileT *__restrict__ templ,
+                                                                 uint64_t tile_base, uint64_t ntiles,
+                                                                 uint32_t per_lane, SnapTabs st,
+                                                                 const ew_cksum_t *__restrict__ slots) {
+  const uint64_t g = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+  uint64_t i = g * per_lane;
+  const uint64_t end = (i + per_lane < ntiles) ? i + per_lane : ntiles;
+  if (i >= end) return;
+  uint32_t key_rank = 0;
+  uint64_t key_blk = 0, sum = 0, xr = 0;
+  bool open = false;
+  for (; i < end; ++i) {
+    const ew::TileRef tl = ew::decode_tile(runs, nruns, templ, tile_base + i);
+    const uint64_t blk = (tl.dst_off * ES) >> 20;
+    if (open && (tl.dst_buf != key_rank || blk != key_blk)) {
+      ew_cksum_t *rec = st.rec[key_rank] + key_blk;
+      atomicAdd(reinterpret_cast<unsigned long long *>(&rec->sum), (unsigned long long)sum);
+      atomicXor(reinterpret_cast<unsigned long long *>(&rec->xr), (unsigned long long)xr);
+      sum = 0;
+      xr = 0;
+    }
+    open = true;
+    key_rank = tl.dst_buf;
+    key_blk = blk;
+    const ew_cksum_t r = slots[i];
+    sum += r.sum;
+    xr ^= r.xr;
+  }
+  ew_cksum_t *rec = st.rec[key_rank] + key_blk;
+  atomicAdd(reinterpret_cast<unsigned long long *>(&rec->sum), (unsigned long long)sum);
+  atomicXor(reinterpret_cast<unsigned long long *>(&rec->xr), (unsigned long long)xr);
+}
+
+// Zeroes every new rank's records: blockIdx.y = rank, 2 words per record.
+__global__ __launch_bounds__(kThreads) void ew_zero_records_kernel(SnapTabs st) {
+  const uint32_t k = blockIdx.y;
+  const uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i < 2ull * st.nblk[k]) reinterpret_cast<uint64_t *>(st.rec[k])[i] = 0;
 }
 
 // Plain copy, one 128-bit vector per lane and 4 KiB per workgroup like the tile copy, no table
@@ -454,11 +629,11 @@ int launch_zero(void *p, uint64_t nbytes, hipStream_t stream) {
 // ---- scratch for the per-workgroup checksum slots --------------------------------------------
 // A fixed device array, so taking a snapshot never allocates.  It is cut into regions, one per
 // stream that uses the library (first come, first served); a call on a stream that finds no free
-// region uses the atomic kernel instead, which needs no scratch.  One region covers 4 GiB of
-// input per pass; longer buffers are processed in several passes on the stream.
+// region uses the atomic kernel instead, which needs no scratch.  One region (32 MiB) covers
+// 8 GiB of input per pass; longer buffers are processed in several passes on the stream.
 constexpr uint32_t kRegions = 4;
-constexpr uint64_t kRegionSlots = 1ull << 20;                       // 16 MiB of 16-byte slots
-constexpr uint64_t kPassBytes = kRegionSlots * 4096;                 // 4 GiB
+constexpr uint64_t kRegionSlots = 1ull << 21;                       // 32 MiB of 16-byte slots
+constexpr uint64_t kPassBytes = kRegionSlots * 4096;                 // 8 GiB
 __device__ __align__(256) ew_cksum_t g_slot_scratch[kRegions * kRegionSlots];
 
 struct ScratchState {
@@ -573,7 +748,13 @@ uint64_t ew_plan_num_tiles(const ew_plan_t *plan, int which, uint32_t elem_size)
   const int e = elem_size == 4 ? 1 : 0;
   if (plan->uploaded) return plan->tables[which][e].ntiles;
   const uint32_t te = g_tile_elems > 0 ? (uint32_t)g_tile_elems : (uint32_t)(g_tile_bytes / elem_size);
-  return ew::count_tiles(*plan, which, te);
+  try {
+    ew::TileTable tt;
+    ew::build_tile_table(*plan, which, te, (uint32_t)(g_tile_align_bytes / elem_size), tt);
+    return tt.ntiles;
+  } catch (const std::bad_alloc &) {
+    return 0;
+  }
 }
 
 int ew_plan_upload(ew_plan_t *plan, uint32_t tile_elems, void *stream) {
@@ -588,7 +769,7 @@ int ew_plan_upload(ew_plan_t *plan, uint32_t tile_elems, void *stream) {
       plan->tile_elems[e] = tile_elems ? tile_elems : (uint32_t)(g_tile_bytes / es);
       for (int w = 0; w < 2; ++w) {
         ew::TileTable &tt = plan->tables[w][e];
-        ew::build_tile_table(*plan, w, plan->tile_elems[e], tt);
+        ew::build_tile_table(*plan, w, plan->tile_elems[e], (uint32_t)(g_tile_align_bytes / es), tt);
         if (tt.ntiles > 0x7fffffffull) {  // tile ids are workgroup ids
           release_tables(plan);
           return EW_EINVAL;
@@ -662,6 +843,64 @@ int ew_unpack(const ew_plan_t *plan, const void *stage, const void *const *old_s
   return launch_segcopy(tt, tabs, elem_size, (hipStream_t)stream);
 }
 
+int ew_unpack_snapshot(const ew_plan_t *plan, const void *stage, const void *const *old_shards,
+                       const void *const *snapshots, void *const *new_shards, void *const *new_snapshots,
+                       ew_cksum_t *const *new_cksums, uint32_t elem_size, void *stream_) {
+  if (!plan || !plan->uploaded || (elem_size != 2 && elem_size != 4)) return EW_EINVAL;
+  const int e = elem_size == 4 ? 1 : 0;
+  const ew::TileTable &tt = plan->tables[1][e];
+  if (tt.ntiles == 0) return EW_OK;
+  if (!new_shards || !new_snapshots || !new_cksums) return EW_EINVAL;
+  if (plan->stage_len > 0 && !stage) return EW_EINVAL;
+  if ((uint64_t)plan->tile_elems[e] * elem_size > EW_CKSUM_BLOCK) return EW_EINVAL;  // a tile spans <= 2 blocks
+  hipStream_t stream = (hipStream_t)stream_;
+  CopyTabs tabs;
+  const int rc = fill_tabs(plan, old_shards, snapshots, tabs, true);
+  if (rc != EW_OK) return rc;
+  tabs.src[ew::kSrcStage] = (const char *)stage;
+  SnapTabs st;
+  std::memset(&st, 0, sizeof(st));
+  uint32_t max_blk = 0;
+  for (uint32_t k = 0; k < plan->new_dp; ++k) {
+    if (plan->new_len[k] == 0) continue;
+    if (!new_shards[k] || !new_snapshots[k] || !new_cksums[k]) return EW_EINVAL;
+    const uint64_t nblk = (plan->new_len[k] * elem_size + EW_CKSUM_BLOCK - 1) / EW_CKSUM_BLOCK;
+    if (nblk > 0xffffffffull) return EW_EINVAL;
+    tabs.dst[k] = (char *)new_shards[k];
+    st.snap[k] = (char *)new_snapshots[k];
+    st.rec[k] = new_cksums[k];
+    st.nblk[k] = (uint32_t)nblk;
+    if (st.nblk[k] > max_blk) max_blk = st.nblk[k];
+  }
+  std::lock_guard<std::mutex> lock(g_scratch.mu);
+  ew_cksum_t *slots = region_for(stream);
+  if (!slots) return EW_ENOMEM;  // every scratch region is owned by another stream
+  hipLaunchKernelGGL(ew_zero_records_kernel, dim3((2 * max_blk + kThreads - 1) / kThreads, plan->new_dp),
+                     dim3(kThreads), 0, stream, st);
+  EW_HIP(hipGetLastError());
+  const uint32_t nruns = (uint32_t)tt.runs.size();
+  const uint32_t per_lane = 16;
+  for (uint64_t t0 = 0; t0 < tt.ntiles; t0 += kRegionSlots) {
+    const uint64_t n = tt.ntiles - t0 < kRegionSlots ? tt.ntiles - t0 : kRegionSlots;
+    const uint64_t fold_grid = ((n + per_lane - 1) / per_lane + kThreads - 1) / kThreads;
+    if (elem_size == 2) {
+      hipLaunchKernelGGL(ew_unpack_snap_kernel<2>, dim3((uint32_t)n), dim3(kThreads), 0, stream, tt.d_runs, nruns,
+                         tt.d_templ, t0, tabs, st, slots);
+      EW_HIP(hipGetLastError());
+      hipLaunchKernelGGL(ew_fold_tiles_kernel<2>, dim3((uint32_t)fold_grid), dim3(kThreads), 0, stream, tt.d_runs,
+                         nruns, tt.d_templ, t0, n, per_lane, st, slots);
+    } else {
+      hipLaunchKernelGGL(ew_unpack_snap_kernel<4>, dim3((uint32_t)n), dim3(kThreads), 0, stream, tt.d_runs, nruns,
+                         tt.d_templ, t0, tabs, st, slots);
+      EW_HIP(hipGetLastError());
+      hipLaunchKernelGGL(ew_fold_tiles_kernel<4>, dim3((uint32_t)fold_grid), dim3(kThreads), 0, stream, tt.d_runs,
+                         nruns, tt.d_templ, t0, n, per_lane, st, slots);
+    }
+    EW_HIP(hipGetLastError());
+  }
+  return EW_OK;
+}
+
 int ew_snapshot(const void *src, void *dst, uint64_t nbytes, ew_cksum_t *cksums, void *stream) {
   if (nbytes == 0) return EW_OK;
   if (!src || !dst || !cksums) return EW_EINVAL;
@@ -716,6 +955,9 @@ int ew_set_param(const char *name, int64_t value) {
   } else if (!std::strcmp(name, "tile_elems")) {
     if (value < 0 || value > (1 << 24)) return EW_EINVAL;
     g_tile_elems = value;
+  } else if (!std::strcmp(name, "tile_align_bytes")) {
+    if (value < 0 || value > 4096 || (value & (value - 1)) || (value && value < 16)) return EW_EINVAL;
+    g_tile_align_bytes = value;
   } else {
     return EW_EINVAL;
   }
@@ -730,6 +972,7 @@ int64_t ew_get_param(const char *name) {
   if (!std::strcmp(name, "cksum_mode")) return g_cksum_mode;
   if (!std::strcmp(name, "tile_elems")) return g_tile_elems;
   if (!std::strcmp(name, "tile_bytes")) return g_tile_bytes;
+  if (!std::strcmp(name, "tile_align_bytes")) return g_tile_align_bytes;
   return -1;
 }
 

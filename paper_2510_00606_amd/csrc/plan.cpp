@@ -175,70 +175,142 @@ void expand_segs(ew_plan_t *p) {
 
 namespace ew {
 
-uint64_t count_tiles(const ew_plan_t &plan, int which, uint32_t tile_elems) {
-  uint64_t n = 0;
-  for (const Run &run : plan.runs) {
-    uint64_t per_unit = 0;
-    for (uint32_t r = run.seg_begin; r < run.seg_end; ++r) {
-      const RunSeg &s = plan.run_segs[r];
-      if (which == 0 && (s.flags & EW_SEG_LOCAL)) continue;
-      per_unit += (s.len + tile_elems - 1) / tile_elems;
-    }
-    n += per_unit * run.n_units;
+// Tile order.  Tiles are numbered destination-major: for unpack, new rank by new rank (each new
+// shard is written front to back); for pack, pair message by pair message in arena order.  Within
+// a destination the runs follow each other, and within a run the units.  The workgroups in flight
+// at any moment then write one sequential stream and read the two or three old shards that
+// overlap it, which is what HBM likes: numbering tiles unit by unit instead makes up to
+// old_dp + new_dp streams advance in lock step at equal offsets of equally sized buffers, and the
+// identity plan of the 7B stage then copies at 4.8 TB/s instead of 6.3 (measured).
+//
+// Tile cuts.  A segment is cut so that every cut point inside it falls on a multiple of
+// align_elems in the DESTINATION buffer (128 bytes by default): the first tile runs from the
+// segment's start to the last such point within tile_elems, the following tiles are full and
+// aligned, the last one takes the rest.  Neighbouring workgroups, which run on different XCDs with
+// separate L2s, then never write parts of the same 128-byte line (measured: 4 % on the copy rate).
+// The phase of a segment's destination offset changes from unit to unit by its stride, so the
+// templates are laid down for a period of P consecutive units after which all phases repeat
+// (P <= 128 bytes / 16 bytes = 8 when unit lengths are multiples of the 8-element granule; a
+// group with a longer period is cut without alignment), and a record's "unit" is that period.
+static uint64_t gcd_u64(uint64_t a, uint64_t b) {
+  while (b) {
+    const uint64_t t = a % b;
+    a = b;
+    b = t;
   }
-  return n;
+  return a;
 }
 
-void build_tile_table(const ew_plan_t &plan, int which, uint32_t tile_elems, TileTable &out) {
+void build_tile_table(const ew_plan_t &plan, int which, uint32_t tile_elems, uint32_t align_elems,
+                      TileTable &out) {
   out.runs.clear();
   out.templ.clear();
   out.ntiles = 0;
-  for (const Run &run : plan.runs) {
-    RunT rt;
-    rt.tile_begin = out.ntiles;
-    rt.templ_begin = (uint32_t)out.templ.size();
+  if (align_elems == 0 || tile_elems % align_elems != 0) align_elems = 1;
+  struct Item {
+    uint32_t key, run, seg;
+  };
+  std::vector<Item> items;
+  for (uint32_t ri = 0; ri < plan.runs.size(); ++ri) {
+    const Run &run = plan.runs[ri];
     for (uint32_t r = run.seg_begin; r < run.seg_end; ++r) {
       const RunSeg &s = plan.run_segs[r];
+      if (which == 0 && (s.flags & EW_SEG_LOCAL)) continue;
+      const uint32_t key = which == 0 ? (uint32_t)s.dst_rank * EW_MAX_DP + s.holder : s.dst_rank;
+      items.push_back({key, ri, r});
+    }
+  }
+  std::stable_sort(items.begin(), items.end(), [](const Item &a, const Item &b) {
+    return a.key != b.key ? a.key < b.key : (a.run != b.run ? a.run < b.run : a.seg < b.seg);
+  });
+
+  struct Piece {  // one segment of the group, as source -> destination of this table
+    uint64_t src, dst, src_stride, dst_stride, len;
+    uint16_t src_buf, dst_buf;
+  };
+  std::vector<Piece> group;
+  size_t i = 0;
+  while (i < items.size()) {
+    const uint32_t key = items[i].key, ri = items[i].run;
+    const Run &run = plan.runs[ri];
+    group.clear();
+    for (; i < items.size() && items[i].key == key && items[i].run == ri; ++i) {
+      const RunSeg &s = plan.run_segs[items[i].seg];
       const bool local = (s.flags & EW_SEG_LOCAL) != 0;
-      if (which == 0 && local) continue;
       const uint16_t data_buf =
           (uint16_t)((s.flags & EW_SEG_SNAPSHOT) ? kSrcSnap + s.src_owner : kSrcLive + s.holder);
-      TileT t;
-      std::memset(&t, 0, sizeof(t));
-      uint64_t src, dst;
+      Piece pc;
+      pc.len = s.len;
       if (which == 0) {  // source buffer -> arena
-        t.src_buf = data_buf;
-        t.dst_buf = (uint16_t)kDstStage;
-        src = s.src_off;
-        dst = s.stage_off;
-        t.src_stride = s.src_stride;
-        t.dst_stride = s.stage_stride;
+        pc.src_buf = data_buf;
+        pc.dst_buf = (uint16_t)kDstStage;
+        pc.src = s.src_off;
+        pc.dst = s.stage_off;
+        pc.src_stride = s.src_stride;
+        pc.dst_stride = s.stage_stride;
       } else if (local) {  // source buffer -> new shard
-        t.src_buf = data_buf;
-        t.dst_buf = s.dst_rank;
-        src = s.src_off;
-        dst = s.dst_off;
-        t.src_stride = s.src_stride;
-        t.dst_stride = s.dst_stride;
+        pc.src_buf = data_buf;
+        pc.dst_buf = s.dst_rank;
+        pc.src = s.src_off;
+        pc.dst = s.dst_off;
+        pc.src_stride = s.src_stride;
+        pc.dst_stride = s.dst_stride;
       } else {  // arena -> new shard
-        t.src_buf = (uint16_t)kSrcStage;
-        t.dst_buf = s.dst_rank;
-        src = s.stage_off;
-        dst = s.dst_off;
-        t.src_stride = s.stage_stride;
-        t.dst_stride = s.dst_stride;
+        pc.src_buf = (uint16_t)kSrcStage;
+        pc.dst_buf = s.dst_rank;
+        pc.src = s.stage_off;
+        pc.dst = s.dst_off;
+        pc.src_stride = s.stage_stride;
+        pc.dst_stride = s.dst_stride;
       }
-      for (uint64_t done = 0; done < s.len; done += tile_elems) {
-        t.src_off = src + done;
-        t.dst_off = dst + done;
-        t.len = (uint32_t)std::min<uint64_t>(tile_elems, s.len - done);
-        out.templ.push_back(t);
+      group.push_back(pc);
+    }
+    // period after which every piece's destination phase repeats
+    uint64_t period = 1, align = align_elems;
+    if (align > 1 && run.n_units > 1) {
+      for (const Piece &pc : group) {
+        const uint64_t ps = align / gcd_u64(pc.dst_stride % align, align);  // stride % align == 0 -> 1
+        period = period / gcd_u64(period, ps) * ps;
+        if (period > 8) break;
+      }
+      if (period > 8) {
+        period = 1;
+        align = 1;
       }
     }
-    rt.tiles_per_unit = (uint32_t)(out.templ.size() - rt.templ_begin);
-    if (rt.tiles_per_unit == 0) continue;
-    out.runs.push_back(rt);
-    out.ntiles += (uint64_t)rt.tiles_per_unit * run.n_units;
+    // lays down `units` consecutive units starting at unit `first` as one record repeated `reps` times
+    auto emit = [&](uint64_t first, uint64_t units, uint64_t reps) {
+      RunT rt;
+      rt.tile_begin = out.ntiles;
+      rt.templ_begin = (uint32_t)out.templ.size();
+      for (uint64_t u = 0; u < units; ++u)
+        for (const Piece &pc : group) {
+          TileT t;
+          std::memset(&t, 0, sizeof(t));
+          t.src_buf = pc.src_buf;
+          t.dst_buf = pc.dst_buf;
+          t.src_stride = pc.src_stride * units;
+          t.dst_stride = pc.dst_stride * units;
+          const uint64_t src = pc.src + (first + u) * pc.src_stride;
+          const uint64_t dst = pc.dst + (first + u) * pc.dst_stride;
+          uint64_t done = 0;
+          while (done < pc.len) {
+            const uint64_t room = tile_elems - (dst + done) % align;  // up to the last aligned point
+            const uint64_t n = std::min<uint64_t>(room, pc.len - done);
+            t.src_off = src + done;
+            t.dst_off = dst + done;
+            t.len = (uint32_t)n;
+            out.templ.push_back(t);
+            done += n;
+          }
+        }
+      rt.tiles_per_unit = (uint32_t)(out.templ.size() - rt.templ_begin);
+      out.runs.push_back(rt);
+      out.ntiles += (uint64_t)rt.tiles_per_unit * reps;
+    };
+    const uint64_t whole = run.n_units / period, rest = run.n_units % period;
+    if (whole > 0) emit(0, period, whole);
+    if (rest > 0) emit(whole * period, rest, 1);
   }
 }
 
@@ -292,13 +364,13 @@ int ew_plan_bounds(uint32_t old_dp, uint32_t new_dp, uint64_t alive_mask, uint64
   return EW_OK;
 }
 
-int ew_plan_tiles(const ew_plan_t *p, int which, uint32_t tile_elems, uint64_t first, uint64_t count,
-                  ew_tile_t *out, uint64_t *total) {
+int ew_plan_tiles(const ew_plan_t *p, int which, uint32_t tile_elems, uint32_t align_elems, uint64_t first,
+                  uint64_t count, ew_tile_t *out, uint64_t *total) {
   if (!p || (which != 0 && which != 1) || tile_elems == 0 || tile_elems > (1u << 24)) return EW_EINVAL;
   if (count > 0 && !out) return EW_EINVAL;
   try {
     ew::TileTable tt;
-    ew::build_tile_table(*p, which, tile_elems, tt);
+    ew::build_tile_table(*p, which, tile_elems, align_elems, tt);
     if (total) *total = tt.ntiles;
     if (count == 0) return EW_OK;
     if (first > tt.ntiles || count > tt.ntiles - first) return EW_EINVAL;

@@ -31,8 +31,8 @@ struct Run {
 
 // ---- device tables ------------------------------------------------------------------------
 // One unit of copy work for a workgroup: at most tile_elems elements of one segment of one
-// unit.  A tile template belongs to a run; for unit i of the run the offsets are
-// off0 + i * stride.  src_buf indexes the source pointer table (kSrcLive + old rank,
+// unit.  A tile template belongs to a record (RunT); for repetition i of the record the offsets
+// are off0 + i * stride.  src_buf indexes the source pointer table (kSrcLive + old rank,
 // kSrcSnap + owner, kSrcStage), dst_buf the destination table (new rank, or kDstStage).
 struct TileT {
   uint64_t src_off, dst_off;        // elements, unit 0 of the run
@@ -43,10 +43,12 @@ struct TileT {
 };
 static_assert(sizeof(TileT) == 48, "tile template must stay 48 bytes");
 
+// One record per (destination, run of equal units): the tiles that destination receives from the
+// run, unit after unit.  Records are ordered destination-major (see build_tile_table).
 struct RunT {
-  uint64_t tile_begin;      // global id of the run's first tile
+  uint64_t tile_begin;      // global id of the record's first tile
   uint32_t tiles_per_unit;  // templates per unit (> 0)
-  uint32_t templ_begin;     // index of the run's first template
+  uint32_t templ_begin;     // index of the record's first template
 };
 static_assert(sizeof(RunT) == 16, "run record must stay 16 bytes");
 
@@ -129,6 +131,7 @@ struct ew_plan_s {
 namespace ew {
 // Cuts the plan's run segments into tile templates.  which = 0: non-LOCAL segments, source ->
 // arena.  which = 1: every segment, arena or local source -> new shard.
-void build_tile_table(const ew_plan_t &plan, int which, uint32_t tile_elems, TileTable &out);
-uint64_t count_tiles(const ew_plan_t &plan, int which, uint32_t tile_elems);
+// Cuts inside a segment fall on multiples of align_elems in the destination buffer (0 or 1: none).
+void build_tile_table(const ew_plan_t &plan, int which, uint32_t tile_elems, uint32_t align_elems,
+                      TileTable &out);
 }  // namespace ew

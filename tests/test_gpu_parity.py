@@ -16,7 +16,7 @@ MIB = 1 << 20
 
 @pytest.fixture(autouse=True)
 def default_params():
-    saved = {k: ew.ew_get_param(k) for k in ("tile_bytes", "tile_elems", "copy_wgs_per_cu", "cksum_sub_bytes", "cksum_wgs_per_cu",
+    saved = {k: ew.ew_get_param(k) for k in ("tile_bytes", "tile_elems", "tile_align_bytes", "copy_wgs_per_cu", "cksum_sub_bytes", "cksum_wgs_per_cu",
                                               "cksum_mode")}
     yield
     for k, v in saved.items():
@@ -169,6 +169,28 @@ def reshard_case(old_dp, new_dp, mask, numel, chunk, elem_size, rng, tile_elems=
         assert n == len(want_new[k])
         assert np.array_equal(np_bits(new[k][:n]), want_new[k]), f"new shard {k} differs"
         assert guard_intact(new[k], n, elem_size)
+
+    # fused form: unpack + snapshot + checksums of the new shards in one pass
+    new2 = [guarded(plan.new_shard_len(k), elem_size) for k in range(new_dp)]
+    snap2 = [guarded(plan.new_shard_len(k), elem_size) for k in range(new_dp)]
+    nblk = [ew.num_blocks(plan.new_shard_len(k) * elem_size) for k in range(new_dp)]
+    ck2 = [torch.full((nb + 1, 2), -1, dtype=torch.int64, device=DEV) for nb in nblk]
+    if tile_elems * elem_size > MIB and numel > 0:   # a tile may span at most two checksum blocks
+        with pytest.raises(ew.EwError) as e:
+            ew.ew_unpack_snapshot(plan, stage, old_dev, snap_dev, new2, snap2, ck2, elem_size, stream())
+        assert e.value.code == ew.EW_EINVAL
+        plan.close()
+        return
+    ew.ew_unpack_snapshot(plan, stage, old_dev, snap_dev, new2, snap2, ck2, elem_size, stream())
+    torch.cuda.synchronize()
+    for k in range(new_dp):
+        n = plan.new_shard_len(k)
+        assert np.array_equal(np_bits(new2[k][:n]), want_new[k]), f"fused: new shard {k} differs"
+        assert np.array_equal(np_bits(snap2[k][:n]), want_new[k]), f"fused: snapshot of new shard {k} differs"
+        assert guard_intact(new2[k], n, elem_size) and guard_intact(snap2[k], n, elem_size)
+        got = ck2[k].cpu().numpy().view(np.uint64)
+        assert np.array_equal(got[:nblk[k]], checksum.block_checksums(want_new[k])), f"fused: checksums of {k} differ"
+        assert (got[nblk[k]] == np.uint64((1 << 64) - 1)).all(), "record past the end was written"
     plan.close()
 
 
@@ -196,6 +218,8 @@ def test_reshard_small_exhaustive(elem_size):
     (6, 4, 0b111111, 999_999, 10_007),        # voluntary shrink, nothing aligned
     (3, 3, 0b101, 500_000, 50_000),           # same degree, one rank replaced from its snapshot
     (5, 9, 0b10101, 800_000, 800_000),        # one unit, two failures, growth
+    (3, 2, 0b111, 2_600_000, 99_992),         # new shards of several checksum blocks, tiles straddling them
+    (2, 3, 0b10, 1_900_003, 70_001),          # ragged units: words split between segments
 ])
 def test_reshard_medium(case, elem_size):
     rng = np.random.default_rng(hash(case) & 0xFFFF)
@@ -263,8 +287,8 @@ def test_snapshot_on_many_streams():
 
 @pytest.mark.timeout(600)
 def test_snapshot_longer_than_one_scratch_pass():
-    """9 GiB + ragged tail: three passes over the 4 GiB scratch region."""
-    nbytes = 9 * (1 << 30) + 3 * MIB + 4096 + 5
+    """17 GiB + ragged tail: three passes over the 8 GiB scratch region."""
+    nbytes = 17 * (1 << 30) + 3 * MIB + 4096 + 5
     src = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
     g = torch.Generator(device=DEV)
     g.manual_seed(11)
@@ -282,7 +306,7 @@ def test_snapshot_longer_than_one_scratch_pass():
     assert torch.equal(src, dst)
     got = ck.cpu().numpy().view(np.uint64)
     # oracle on sampled blocks incl. both sides of every pass boundary and the ragged last block
-    blocks = sorted({0, 1, 4095, 4096, 4097, 8191, 8192, 8193, nb - 2, nb - 1} | set(np.random.default_rng(1).integers(0, nb, 24).tolist()))
+    blocks = sorted({0, 1, 8191, 8192, 8193, 16383, 16384, 16385, nb - 2, nb - 1} | set(np.random.default_rng(1).integers(0, nb, 24).tolist()))
     for b in blocks:
         host = src[b * MIB:min((b + 1) * MIB, nbytes)].cpu().numpy()
         assert np.array_equal(got[b], checksum.block_checksums(host)[0]), f"block {b}"

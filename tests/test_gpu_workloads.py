@@ -4,10 +4,15 @@
   tiny, 7b_stage      every array compared element by element with the oracle's result
   7b_rank_snapshot    snapshot bytes + every checksum record against the oracle; one flipped bit
                       must be located (block index and bit lane)
-  13b_stage, 70b_stage  bf16 array compared element by element; for the fp32 arrays, sampled
-                      elements of every new shard (incl. both ends) are recomputed one by one by
-                      the oracle's locator from the seeded generator, and the multiset of 64-bit
-                      words is shown to be conserved (wrapping sums of w and w*w, torch integer ops)
+  13b_stage           every array compared element by element with the oracle's result
+  70b_stage           bf16 array compared element by element; for the fp32 arrays (34 GB each),
+                      sampled elements of every new shard (incl. both ends) are recomputed one by
+                      one by the oracle's locator from the seeded generator, and the multiset of
+                      64-bit words is shown to be conserved (wrapping sums of w and w*w, torch
+                      integer ops)
+Every workload also runs the fused ew_unpack_snapshot: new shards and snapshot copies equal the
+verified result, checksums equal the oracle's (all blocks where the oracle result is on the host,
+sampled blocks otherwise).
 """
 import gc
 
@@ -94,6 +99,7 @@ def run_workload_array(w, arr, plan, starts, full_compare, snapshot_all):
         got = synth.to_numpy_bits(new[k][torch.from_numpy(offs).to(DEV)])
         assert np.array_equal(got, want), f"{w.name} {arr}: sampled elements of new shard {k} differ"
     # (3) everything, element by element
+    want_new = None
     if full_compare:
         o_sh = [h if alive[j] else None for j, h in enumerate(host_old)]
         o_sn = [None if alive[j] else h for j, h in enumerate(host_old)]
@@ -101,8 +107,31 @@ def run_workload_array(w, arr, plan, starts, full_compare, snapshot_all):
         want_new = layout.slice_flat(flat, w.new_dp, starts)
         for k in range(w.new_dp):
             assert np.array_equal(synth.to_numpy_bits(new[k]), want_new[k]), f"{w.name} {arr}: new shard {k} differs"
-        del want_new, flat
-    del old, snaps, stage, new
+        del flat
+
+    # (4) the fused form: same new shards, snapshot copies equal to them, checksums = the oracle's
+    new2 = [torch.empty_like(t) for t in new]
+    snap2 = [torch.empty_like(t) for t in new]
+    for t in new2 + snap2:
+        t.view(torch.uint8).fill_(0xA5)
+    ck2 = [torch.full((ew.num_blocks(t.numel() * es), 2), -1, dtype=torch.int64, device=DEV) for t in new]
+    ew.ew_unpack_snapshot(plan, stage, old, snaps, new2, snap2, ck2, es, st)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng([w.seed, 7, synth.ARRAYS.index(arr)])
+    for k in range(w.new_dp):
+        view = torch.int16 if es == 2 else torch.int32
+        assert torch.equal(new2[k].view(view), new[k].view(view)), f"{w.name} {arr}: fused new shard {k} differs"
+        assert torch.equal(snap2[k].view(view), new[k].view(view)), f"{w.name} {arr}: fused snapshot {k} differs"
+        got = ck2[k].cpu().numpy().view(np.uint64)
+        nb = got.shape[0]
+        if want_new is not None:
+            assert np.array_equal(got, checksum.block_checksums(want_new[k])), f"{w.name} {arr}: fused checksums {k}"
+        else:  # sampled blocks (both ends included), bytes taken from the verified new shard
+            raw = new[k].view(torch.uint8)
+            for b in sorted({0, nb - 1} | set(rng.integers(0, nb, 48).tolist())):
+                host = raw[b << 20:min((b + 1) << 20, raw.numel())].cpu().numpy()
+                assert np.array_equal(got[b], checksum.block_checksums(host)[0]), f"{w.name} {arr}: rank {k} block {b}"
+    del old, snaps, stage, new, new2, snap2, want_new
     free()
 
 
@@ -129,7 +158,7 @@ def test_7b_stage_all_arrays():
 
 @pytest.mark.timeout(900)
 def test_13b_stage():
-    run_workload("13b_stage", ("P",), True)
+    run_workload("13b_stage", synth.ARRAYS, True)
 
 
 @pytest.mark.timeout(900)

@@ -263,10 +263,10 @@ def seg_records(segs, which):
     return out
 
 
-def check_tiles(p, tile_elems):
+def check_tiles(p, tile_elems, align=0):
     segs = p.segs()
     for which in (0, 1):
-        t = p.tiles(which, tile_elems)
+        t = p.tiles(which, tile_elems, align)
         assert (t["len"] > 0).all() and (t["len"] <= tile_elems).all()
         got = expand([(int(x["src_buf"]), int(x["src_off"]), int(x["dst_buf"]), int(x["dst_off"]), int(x["len"]))
                       for x in t])
@@ -283,6 +283,8 @@ def test_tiles_cover_segments_exactly():
         p = ew.ew_plan(Do, Dn, mask, N, C)
         for te in (1, 7, 64, 100, 1024, 1 << 20):
             check_tiles(p, te)
+        for te, al in ((64, 8), (64, 32), (1024, 32), (2048, 64), (256, 256), (100, 32)):
+            check_tiles(p, te, al)
     # explicit boundaries with many different unit lengths: many runs, some of them repeated
     rng = np.random.default_rng(3)
     lens = rng.choice([0, 8, 24, 100, 100, 100, 264, 264, 1000], size=60)
@@ -291,7 +293,33 @@ def test_tiles_cover_segments_exactly():
     assert 1 < p.num_runs <= 60
     for te in (16, 100, 4096):
         check_tiles(p, te)
-    assert p.num_tiles(0, 4) == len(p.tiles(0, 1024)) and p.num_tiles(1, 2) == len(p.tiles(1, 2048))
+        check_tiles(p, te, 16)
+    assert p.num_tiles(0, 4) == len(p.tiles(0, 1024, 32)) and p.num_tiles(1, 2) == len(p.tiles(1, 2048, 64))
+
+
+def test_aligned_cuts_fall_on_destination_lines():
+    """With the default 128-byte alignment every cut inside a segment is on a 128-byte multiple of
+    the destination, and tiles of one destination follow each other front to back."""
+    w = configs.stage_7b()
+    p = ew.ew_plan(w.old_dp, w.new_dp, w.alive_mask, 40 * w.chunk + 65536, w.chunk)
+    segs = p.segs()
+    for es, te, al in ((4, 1024, 32), (2, 2048, 64)):
+        for which in (0, 1):
+            t = p.tiles(which, te, al)
+            check = expand([(int(x["src_buf"]), int(x["src_off"]), int(x["dst_buf"]), int(x["dst_off"]), int(x["len"]))
+                            for x in t])
+            want = expand(seg_records(segs, which))
+            assert (check == want).all()
+            # segment starts in destination space
+            starts = {(int(r[2]), int(r[3])) for r in seg_records(segs, which)}
+            for x in t:
+                if (int(x["dst_buf"]), int(x["dst_off"])) not in starts:
+                    assert int(x["dst_off"]) % al == 0
+            # destination-major, ascending inside a destination
+            key = t["dst_buf"].astype(np.int64) * (1 << 44) + t["dst_off"].astype(np.int64)
+            assert (np.diff(key) > 0).all()
+            # few partial tiles: at most two per segment
+            assert len(t) <= int(np.ceil(sum(r[4] for r in seg_records(segs, which)) / te)) + 2 * len(segs)
 
 
 def test_uniform_chunk_plans_are_two_runs():
@@ -305,9 +333,7 @@ def test_uniform_chunk_plans_are_two_runs():
         te = 4096 // es
         total = p.num_tiles(which, es)
         for first in (0, total // 2, total - 5):
-            out = np.zeros(5, ew.TILE_DTYPE)
-            rc = binding.lib().ew_plan_tiles(p.handle, which, te, first, 5, out.ctypes.data, None)
-            assert rc == 0
+            out = p.tiles(which, te, 128 // es, first, 5)
             for x in out:
                 sb, db = int(x["src_buf"]), int(x["dst_buf"])
                 src_cap = p.stage_len if sb == 128 else p.old_shard_len(sb % 64)
