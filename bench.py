@@ -37,6 +37,7 @@ def parse():
     ap.add_argument("--workload", default="7b_stage", choices=["tiny", "7b_stage", "13b_stage"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--unfused", action="store_true", help="run a6 (ew_unpack) and a7 (ew_snapshot) as separate passes")
+    ap.add_argument("--no-migration", action="store_true", help="skip the layer-migration comparison (Sec. 6.3)")
     ap.add_argument("--cpu-sample-units", type=int, default=8192)
     return ap.parse_args()
 
@@ -313,7 +314,63 @@ def main():
                       f"numpy oracle snapshot+checksum, verify, reconstruct+slice, snapshot+checksum of the result; "
                       f"{cpu_s:.1f} s on one host core",
         }
+    # ---------------- layer migration, contiguous vs interleaved assignment (Sec. 6.3); not part of `value`
+    if not args.no_migration and w.name != "tiny":
+        del old, snap, sums, stage, new, nsnap, nsums, got, old_after, snap_used
+        torch.cuda.empty_cache()
+        out["layer_migration"] = migration_compare(ew, configs, synth, torch, st, dev)
     print(json.dumps(out))
+
+
+def migration_compare(ew, configs, synth, torch, st, dev):
+    """Moves one Llama-7B-shaped layer between two 4-layer stages at DP 8 under both ZeRO assignments,
+    all four state arrays, and reports what crosses between ranks (the arena) and how long the send
+    side (ew_pack) and the whole move (ew_pack + ew_unpack) take on this GPU."""
+    import numpy as np
+    D = 8
+    wl = configs.Workload("migrate", 9, configs.stage_tensors(4096, 11008, 4), D, D, 0xFF, 262144, snap_to_tensors=True)
+    starts = wl.unit_starts()
+    per_layer = (len(starts) - 1) // 4
+    layer_elems = int(starts[per_layer])
+    res = {"stage": "2 stages x 4 Llama-7B-shaped layers, DP 8, one layer (|O_i| = %d elements x 14 B) moves" % layer_elems}
+    for name, assignment in (("interleaved", ew.EW_ASSIGN_INTERLEAVED), ("contiguous", ew.EW_ASSIGN_CONTIGUOUS)):
+        plan = ew.ew_plan_migrate(assignment, D, starts, starts, per_layer)
+        ew.ew_plan_upload(plan, 0, st)
+        pack_ms = unpack_ms = 0.0
+        for a in synth.ARRAYS:
+            esz = synth.ELEM_SIZE[a]
+            dt = synth.TORCH_DTYPE[a]
+            old = [synth.fill(wl.seed, r, a, 0, plan.old_shard_len(r), dev) for r in range(2 * D)]
+            new = [torch.empty(plan.new_shard_len(r), dtype=dt, device=dev) for r in range(2 * D)]
+            arena = torch.empty(max(plan.stage_len, 1), dtype=dt, device=dev)
+            tp, tu = [], []
+            for rep in range(4):
+                e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+                e[0].record()
+                ew.ew_pack(plan, old, None, arena, esz, st)
+                e[1].record()
+                ew.ew_unpack(plan, arena, old, None, new, esz, st)
+                e[2].record()
+                torch.cuda.synchronize()
+                if rep:
+                    tp.append(e[0].elapsed_time(e[1]))
+                    tu.append(e[1].elapsed_time(e[2]))
+            pack_ms += sorted(tp)[1]
+            unpack_ms += sorted(tu)[1]
+            del old, new, arena
+            torch.cuda.empty_cache()
+        pairs = sum(1 for h in range(2 * D) for k in range(2 * D) if plan.pair_len(h, k))
+        cross = sum(plan.pair_len(h, k) for h in range(D) for k in range(D, 2 * D))
+        res[name] = {"messages": pairs, "moved_between_ranks_elems": plan.stage_len, "cross_stage_elems": cross,
+                     "moved_over_layer": round(plan.stage_len / layer_elems, 4),
+                     "arena_GB": round(14 * plan.stage_len / 1e9, 3), "pack_ms": round(pack_ms, 3),
+                     "pack_plus_unpack_ms": round(pack_ms + unpack_ms, 3)}
+        plan.close()
+    res["contiguous_over_interleaved_bytes"] = round(res["contiguous"]["moved_between_ranks_elems"] /
+                                                     res["interleaved"]["moved_between_ranks_elems"], 3)
+    res["contiguous_over_interleaved_pack_time"] = round(res["contiguous"]["pack_ms"] / res["interleaved"]["pack_ms"], 3)
+    res["paper_closed_form"] = "interleaved |O_i| in D sends; contiguous |O_i| + (D-1)/2 |O_i| per stage"
+    return res
 
 
 if __name__ == "__main__":

@@ -92,6 +92,25 @@ int ew_plan(uint32_t old_dp, uint32_t new_dp, uint64_t alive_mask, uint64_t nume
 int ew_plan_bounds(uint32_t old_dp, uint32_t new_dp, uint64_t alive_mask, uint64_t n_units,
                    const uint64_t *unit_starts, ew_plan_t **out);
 
+/* ---- Layer migration between two pipeline stages of equal DP degree (Sec. 6.3, Fig. 10) ------
+ * The last n_move units (layers) of stage S become the first units of stage S+1.  Both stages
+ * use the same ZeRO assignment:
+ *   EW_ASSIGN_INTERLEAVED  every unit is split uniformly over the dp ranks of the stage that
+ *                          holds it; rank j's shard is its piece of every unit (Fig. 10b);
+ *   EW_ASSIGN_CONTIGUOUS   a stage's units form one flat array cut into dp contiguous blocks of
+ *                          (about) equal size, block r belonging to rank r (Fig. 10a).
+ * The plan has 2*dp old and 2*dp new ranks: ranks 0..dp-1 are stage S, dp..2dp-1 stage S+1, all
+ * alive.  It is executed by ew_pack / ew_unpack like any other plan (pointer arrays of 2*dp
+ * entries); ew_plan_pair_len(h, k) is the traffic matrix: under the interleaved assignment only
+ * the dp pairs (j, dp + j) are non-empty and sum to the moved state, under the contiguous one
+ * both stages also re-compact ((dp-1)/2 of the moved state per stage when a small layer moves).
+ * src/dst_unit_starts: host arrays of n_units+1 ascending boundaries starting at 0.
+ * EW_EINVAL: unknown assignment, dp = 0, 2*dp > 64, n_move > n_src_units, bad boundaries. */
+#define EW_ASSIGN_INTERLEAVED 0u
+#define EW_ASSIGN_CONTIGUOUS 1u
+int ew_plan_migrate(uint32_t assignment, uint32_t dp, uint64_t n_src_units, const uint64_t *src_unit_starts,
+                    uint64_t n_dst_units, const uint64_t *dst_unit_starts, uint64_t n_move, ew_plan_t **out);
+
 /* Frees host and device tables.  Work enqueued with this plan must have completed. */
 void ew_plan_free(ew_plan_t *plan);
 

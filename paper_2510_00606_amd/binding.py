@@ -40,6 +40,8 @@ _lib = None
 _SIGNATURES = {
     "ew_plan": (C.c_int, [C.c_uint32, C.c_uint32, C.c_uint64, C.c_uint64, C.c_uint64, C.POINTER(C.c_void_p)]),
     "ew_plan_bounds": (C.c_int, [C.c_uint32, C.c_uint32, C.c_uint64, C.c_uint64, C.c_void_p, C.POINTER(C.c_void_p)]),
+    "ew_plan_migrate": (C.c_int, [C.c_uint32, C.c_uint32, C.c_uint64, C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64,
+                                  C.POINTER(C.c_void_p)]),
     "ew_plan_free": (None, [C.c_void_p]),
     "ew_plan_numel": (C.c_uint64, [C.c_void_p]),
     "ew_plan_old_dp": (C.c_uint32, [C.c_void_p]),
@@ -215,6 +217,20 @@ def ew_plan_bounds(old_dp, new_dp, alive_mask, unit_starts) -> Plan:
     out = C.c_void_p()
     _check(lib().ew_plan_bounds(old_dp, new_dp, alive_mask, len(starts) - 1, starts.ctypes.data, C.byref(out)),
            "ew_plan_bounds")
+    return Plan(out.value)
+
+
+EW_ASSIGN_INTERLEAVED, EW_ASSIGN_CONTIGUOUS = 0, 1
+
+
+def ew_plan_migrate(assignment: int, dp: int, src_unit_starts, dst_unit_starts, n_move: int) -> Plan:
+    src = np.ascontiguousarray(src_unit_starts, dtype=np.uint64)
+    dst = np.ascontiguousarray(dst_unit_starts, dtype=np.uint64)
+    if src.ndim != 1 or dst.ndim != 1 or len(src) < 1 or len(dst) < 1:
+        raise ValueError("unit boundary arrays must hold n_units+1 values")
+    out = C.c_void_p()
+    _check(lib().ew_plan_migrate(assignment, dp, len(src) - 1, src.ctypes.data, len(dst) - 1, dst.ctypes.data, n_move,
+                                 C.byref(out)), "ew_plan_migrate")
     return Plan(out.value)
 
 

@@ -38,23 +38,50 @@ struct Builder {
     pair_unit.assign((size_t)p->old_dp * p->new_dp, 0);
   }
 
-  // n consecutive units of L elements each
+  // n consecutive units of L elements each, every one split over all old ranks and all new ranks
   void add_run(uint64_t L, uint64_t n) {
     if (L == 0 || n == 0) return;
-    const uint32_t Do = p->old_dp, Dn = p->new_dp;
-    uint64_t ob[EW_MAX_DP + 1], nb[EW_MAX_DP + 1];
-    piece_bounds(L, Do, ob);
-    piece_bounds(L, Dn, nb);
+    PieceList o, w;
+    o.uniform(L, p->old_dp, 0, 0);
+    w.uniform(L, p->new_dp, 0, 0);
+    add_pieces(L, n, o, w);
+  }
+
+  // An ownership of one unit: piece i covers [b[i], b[i+1]) and belongs to rank r[i].  A rank owns
+  // at most one piece of a unit.
+  struct PieceList {
+    uint64_t b[EW_MAX_DP + 2];
+    uint16_t r[EW_MAX_DP + 1];
+    uint32_t n = 0;
+    // appends the uniform split of [base, base + L) over ranks rank0 .. rank0 + D - 1
+    void uniform(uint64_t L, uint32_t D, uint64_t base, uint32_t rank0) {
+      uint64_t pb[EW_MAX_DP + 1];
+      piece_bounds(L, D, pb);
+      for (uint32_t j = 0; j < D; ++j) {
+        b[n] = base + pb[j];
+        r[n] = (uint16_t)(rank0 + j);
+        ++n;
+      }
+      b[n] = base + L;
+    }
+  };
+
+  // n consecutive units of L elements each with the given old and new ownership
+  void add_pieces(uint64_t L, uint64_t n, const PieceList &o, const PieceList &w) {
+    if (L == 0 || n == 0) return;
+    const uint32_t Dn = p->new_dp;
+    const uint64_t *ob = o.b, *nb = w.b;
     ew::Run run;
     run.n_units = n;
     run.unit_len = L;
     run.seg_begin = (uint32_t)p->run_segs.size();
     std::fill(pair_unit.begin(), pair_unit.end(), 0);
-    uint32_t j = 0, k = 0;
-    while (j < Do && k < Dn) {
-      const uint64_t lo = std::max(ob[j], nb[k]);
-      const uint64_t hi = std::min(ob[j + 1], nb[k + 1]);
+    uint32_t oi = 0, ni = 0;
+    while (oi < o.n && ni < w.n) {
+      const uint64_t lo = std::max(ob[oi], nb[ni]);
+      const uint64_t hi = std::min(ob[oi + 1], nb[ni + 1]);
       if (lo < hi) {
+        const uint32_t j = o.r[oi], k = w.r[ni];
         ew::RunSeg s;
         std::memset(&s, 0, sizeof(s));
         const bool owner_alive = (p->alive_mask >> j) & 1u;
@@ -63,10 +90,10 @@ struct Builder {
         s.holder = (uint16_t)h;
         s.dst_rank = (uint16_t)k;
         s.len = hi - lo;
-        s.src_off = old_cur[j] + (lo - ob[j]);
-        s.dst_off = new_cur[k] + (lo - nb[k]);
-        s.src_stride = ob[j + 1] - ob[j];
-        s.dst_stride = nb[k + 1] - nb[k];
+        s.src_off = old_cur[j] + (lo - ob[oi]);
+        s.dst_off = new_cur[k] + (lo - nb[ni]);
+        s.src_stride = ob[oi + 1] - ob[oi];
+        s.dst_stride = nb[ni + 1] - nb[ni];
         if (!owner_alive) {
           s.flags |= EW_SEG_SNAPSHOT;
           p->snap_read |= 1ull << j;
@@ -84,21 +111,34 @@ struct Builder {
         }
         p->run_segs.push_back(s);
       }
-      const uint64_t oe = ob[j + 1], ne = nb[k + 1];
-      if (oe <= ne) ++j;
-      if (ne <= oe) ++k;
+      const uint64_t oe = ob[oi + 1], ne = nb[ni + 1];
+      if (oe <= ne) ++oi;
+      if (ne <= oe) ++ni;
     }
     run.seg_end = (uint32_t)p->run_segs.size();
     for (uint32_t i = run.seg_begin; i < run.seg_end; ++i) {
       ew::RunSeg &s = p->run_segs[i];
       if (!(s.flags & EW_SEG_LOCAL)) s.stage_stride = pair_unit[(size_t)s.holder * Dn + s.dst_rank];
     }
-    for (uint32_t r = 0; r < Do; ++r) old_cur[r] += n * (ob[r + 1] - ob[r]);
-    for (uint32_t r = 0; r < Dn; ++r) new_cur[r] += n * (nb[r + 1] - nb[r]);
+    for (uint32_t i = 0; i < o.n; ++i) old_cur[o.r[i]] += n * (ob[i + 1] - ob[i]);
+    for (uint32_t i = 0; i < w.n; ++i) new_cur[w.r[i]] += n * (nb[i + 1] - nb[i]);
     for (size_t i = 0; i < pair_cur.size(); ++i) pair_cur[i] += n * pair_unit[i];
     p->numel += n * L;
     p->num_segs += n * (uint64_t)(run.seg_end - run.seg_begin);
     if (run.seg_end > run.seg_begin) p->runs.push_back(run);
+  }
+
+  // runs of equal-length units among units [u0, u1) of a boundary array, all with one ownership rule
+  template <class Add>
+  void for_runs(const uint64_t *starts, uint64_t u0, uint64_t u1, Add add) {
+    uint64_t u = u0;
+    while (u < u1) {
+      const uint64_t L = starts[u + 1] - starts[u];
+      uint64_t v = u + 1;
+      while (v < u1 && starts[v + 1] - starts[v] == L) ++v;
+      add(L, v - u);
+      u = v;
+    }
   }
 
   void finish() {
@@ -347,13 +387,59 @@ int ew_plan_bounds(uint32_t old_dp, uint32_t new_dp, uint64_t alive_mask, uint64
   if (rc != EW_OK) return rc;
   try {
     Builder b(p);
-    uint64_t u = 0;
-    while (u < n_units) {  // runs of equal-length units
-      const uint64_t L = unit_starts[u + 1] - unit_starts[u];
-      uint64_t v = u + 1;
-      while (v < n_units && unit_starts[v + 1] - unit_starts[v] == L) ++v;
-      b.add_run(L, v - u);
-      u = v;
+    b.for_runs(unit_starts, 0, n_units, [&](uint64_t L, uint64_t n) { b.add_run(L, n); });
+    b.finish();
+  } catch (const std::bad_alloc &) {
+    delete p;
+    return EW_ENOMEM;
+  }
+  *out = p;
+  return EW_OK;
+}
+
+int ew_plan_migrate(uint32_t assignment, uint32_t dp, uint64_t n_src_units, const uint64_t *src_unit_starts,
+                    uint64_t n_dst_units, const uint64_t *dst_unit_starts, uint64_t n_move, ew_plan_t **out) {
+  if (assignment != EW_ASSIGN_INTERLEAVED && assignment != EW_ASSIGN_CONTIGUOUS) return EW_EINVAL;
+  if (dp == 0 || 2 * dp > EW_MAX_DP || !src_unit_starts || !dst_unit_starts) return EW_EINVAL;
+  if (src_unit_starts[0] != 0 || dst_unit_starts[0] != 0 || n_move > n_src_units) return EW_EINVAL;
+  for (uint64_t u = 0; u < n_src_units; ++u)
+    if (src_unit_starts[u + 1] < src_unit_starts[u]) return EW_EINVAL;
+  for (uint64_t u = 0; u < n_dst_units; ++u)
+    if (dst_unit_starts[u + 1] < dst_unit_starts[u]) return EW_EINVAL;
+  // ranks 0..dp-1 are stage S, dp..2dp-1 stage S+1, before and after; everybody is alive
+  ew_plan_t *p = nullptr;
+  const uint64_t all = 2 * dp == 64 ? ~0ull : ((1ull << (2 * dp)) - 1);
+  const int rc = new_plan(2 * dp, 2 * dp, all, &p);
+  if (rc != EW_OK) return rc;
+  try {
+    Builder b(p);
+    using PL = Builder::PieceList;
+    const uint64_t keep = n_src_units - n_move;
+    if (assignment == EW_ASSIGN_INTERLEAVED) {
+      // every layer is split over the ranks of the stage that holds it (Fig. 10b): a moved layer's
+      // piece j goes from rank j of stage S to rank j of stage S+1, nothing else changes owner
+      auto add = [&](uint32_t old0, uint32_t new0) {
+        return [&b, dp, old0, new0](uint64_t L, uint64_t n) {
+          PL o, w;
+          o.uniform(L, dp, 0, old0);
+          w.uniform(L, dp, 0, new0);
+          b.add_pieces(L, n, o, w);
+        };
+      };
+      b.for_runs(src_unit_starts, 0, keep, add(0, 0));
+      b.for_runs(src_unit_starts, keep, n_src_units, add(0, dp));
+      b.for_runs(dst_unit_starts, 0, n_dst_units, add(dp, dp));
+    } else {
+      // each stage keeps one flat array cut into dp contiguous blocks (Fig. 10a): the two arrays,
+      // laid end to end, form one unit whose cuts all move when the layers change sides
+      const uint64_t A = src_unit_starts[n_src_units], B = dst_unit_starts[n_dst_units];
+      const uint64_t M = A - src_unit_starts[keep];
+      PL o, w;
+      o.uniform(A, dp, 0, 0);
+      o.uniform(B, dp, A, dp);
+      w.uniform(A - M, dp, 0, 0);
+      w.uniform(B + M, dp, A - M, dp);
+      b.add_pieces(A + B, 1, o, w);
     }
     b.finish();
   } catch (const std::bad_alloc &) {

@@ -340,3 +340,96 @@ def test_uniform_chunk_plans_are_two_runs():
                 dst_cap = p.stage_len if db == 64 else p.new_shard_len(db)
                 assert int(x["src_off"]) + int(x["len"]) <= src_cap
                 assert int(x["dst_off"]) + int(x["len"]) <= dst_cap
+
+
+# ------------------------------------------------------------------ layer migration plans (Sec. 6.3)
+def apply_segs(p, old_shards, snaps=None):
+    """What pack + unpack must produce, replayed on the host from the explicit segment table."""
+    segs = p.segs()
+    dt = old_shards[0].dtype
+    stage = np.zeros(p.stage_len, dt)
+    new = [np.zeros(p.new_shard_len(k), dt) for k in range(p.new_dp)]
+    wrote = [np.zeros(p.new_shard_len(k), np.int8) for k in range(p.new_dp)]
+    for s in segs:
+        src = snaps[int(s["src_owner"])] if s["flags"] & ew.EW_SEG_SNAPSHOT else old_shards[int(s["holder"])]
+        a, n = int(s["src_off"]), int(s["len"])
+        data = src[a:a + n]
+        if not s["flags"] & ew.EW_SEG_LOCAL:
+            stage[int(s["stage_off"]):int(s["stage_off"]) + n] = data
+            data = stage[int(s["stage_off"]):int(s["stage_off"]) + n]
+        k, d = int(s["dst_rank"]), int(s["dst_off"])
+        new[k][d:d + n] = data
+        wrote[k][d:d + n] += 1
+    assert all((w == 1).all() for w in wrote)
+    return new
+
+
+@pytest.mark.parametrize("assignment", [ew.EW_ASSIGN_INTERLEAVED, ew.EW_ASSIGN_CONTIGUOUS])
+def test_migrate_plan_equals_oracle(assignment):
+    from oracle import migrate
+    rng = np.random.default_rng(assignment)
+    cases = [(3, [0, 100, 364, 1000], [0, 264, 500], 2), (4, [0, 8, 16, 4099], [0, 7], 1), (2, [0, 50, 120], [0, 30, 90, 91], 0),
+             (5, [0, 1000], [0, 24, 48], 1), (4, list(range(0, 4097, 256)), list(range(0, 2049, 256)), 5),
+             (8, list(range(0, 64 * 641, 640)), list(range(0, 64 * 321, 640)), 7), (1, [0, 9, 30], [0, 5], 2),
+             (32, [0, 5000, 10000], [0, 5000], 1)]
+    for D, src, dst, n_move in cases:
+        src, dst = np.asarray(src, np.int64), np.asarray(dst, np.int64)
+        s_iv = migrate.rank_intervals(src, D, assignment)
+        d_iv = migrate.rank_intervals(dst, D, assignment)
+        s_sh = [rng.integers(0, 1 << 40, sum(h - l for l, h in x)) for x in s_iv]
+        d_sh = [rng.integers(0, 1 << 40, sum(h - l for l, h in x)) for x in d_iv]
+        want_s, want_d = migrate.migrate(s_sh, d_sh, src, dst, D, assignment, n_move)
+        p = ew.ew_plan_migrate(assignment, D, src, dst, n_move)
+        assert p.old_dp == p.new_dp == 2 * D
+        assert [p.old_shard_len(r) for r in range(2 * D)] == [len(x) for x in s_sh + d_sh]
+        assert [p.new_shard_len(r) for r in range(2 * D)] == [len(x) for x in want_s + want_d]
+        got = apply_segs(p, s_sh + d_sh)
+        for a, b in zip(got, want_s + want_d):
+            assert np.array_equal(a, b)
+        # traffic matrix = the oracle's ownership-change matrix
+        m = migrate.traffic(src, dst, D, assignment, n_move)
+        segs = p.segs()
+        for h in range(2 * D):
+            for k in range(2 * D):
+                if h != k:
+                    assert p.pair_len(h, k) == m[h, k]
+                else:
+                    sel = segs[(segs["holder"] == h) & (segs["dst_rank"] == k)]
+                    assert int(sel["len"].sum()) == m[h, k]
+        check_invariants(p, 2 * D, 2 * D, (1 << (2 * D)) - 1, int(src[-1] + dst[-1]))
+        for te, al in ((64, 0), (1024, 32)):
+            check_tiles(p, te, al)
+
+
+def test_migrate_closed_forms_at_the_paper_degree():
+    # Llama2-34B workload of the paper: DP 3 (Table 2); one layer of the 7B shape stands in for |O_i|
+    layer = sum(configs.llama_layer_tensors(4096, 11008))
+    D = 3
+    units = 24
+    L = layer // units              # 8 432 640: a multiple of 8 * D
+    assert L * units == layer and L % (8 * D * D) == 0
+    src = np.arange(4 * units + 1, dtype=np.uint64) * L   # 4 layers on stage S
+    dst = np.arange(4 * units + 1, dtype=np.uint64) * L   # 4 layers on stage S+1
+    pi = ew.ew_plan_migrate(ew.EW_ASSIGN_INTERLEAVED, D, src, dst, units)
+    pc = ew.ew_plan_migrate(ew.EW_ASSIGN_CONTIGUOUS, D, src, dst, units)
+    pairs = {(h, k): pi.pair_len(h, k) for h in range(2 * D) for k in range(2 * D) if pi.pair_len(h, k)}
+    assert pairs == {(j, D + j): layer // D for j in range(D)}        # exactly D 1:1 sends summing to |O_i|
+    assert pi.stage_len == layer
+    cross = sum(pc.pair_len(h, k) for h in range(D) for k in range(D, 2 * D))
+    intra_s = sum(pc.pair_len(h, k) for h in range(D) for k in range(D))
+    intra_d = sum(pc.pair_len(h, k) for h in range(D, 2 * D) for k in range(D, 2 * D))
+    assert cross == layer and 2 * intra_s == (D - 1) * layer and 2 * intra_d == (D - 1) * layer
+    assert 2 * (cross + intra_s) == (D + 1) * layer                    # the paper's (D+1)/2 |O_i|
+    assert pi.num_runs == 3 and pc.num_runs == 1
+
+
+def test_migrate_errors():
+    def code(*a):
+        with pytest.raises(ew.EwError) as e:
+            ew.ew_plan_migrate(*a)
+        return e.value.code
+    assert code(2, 4, [0, 8], [0, 8], 1) == ew.EW_EINVAL          # unknown assignment
+    assert code(0, 0, [0, 8], [0, 8], 1) == ew.EW_EINVAL
+    assert code(0, 33, [0, 8], [0, 8], 1) == ew.EW_EINVAL         # 2*dp > 64
+    assert code(0, 4, [0, 8], [0, 8], 2) == ew.EW_EINVAL          # more layers than the stage has
+    assert code(1, 4, [0, 8, 4], [0, 8], 1) == ew.EW_EINVAL
