@@ -9,8 +9,9 @@ One step = one pass over one DP group's state (all four arrays P/W/M/V resident 
   a6+a7        ew_unpack_snapshot: arena + local segments -> new shards, their snapshot copies and
                the checksums of the new shards, every element read once
                (--unfused: ew_unpack, then ew_snapshot of every new rank's partition)
-`value` is the algorithmic bytes (read + written) of the kernels as run divided by the step's
-wall time; `ms_per_step` is the figure that shows what fusing a6 and a7 saves.
+`value` is the algorithmic bytes (read + written) of the kernels as run divided by the step's wall
+time; `ms_per_step` is the figure that shows what fusing a6 and a7 saves.  The path not chosen for
+the headline is timed too, after the timed region, and reported under "other_path".
 
 Prints ONE JSON line.  --gpus above 1 is refused: this build is one GPU only.
 """
@@ -28,6 +29,12 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
 
+KERNEL_OF = {"snapshot_old": "ew_cksum_slots_kernel<copy> (+ ew_fold_kernel) = ew_snapshot",
+             "snapshot_new": "ew_cksum_slots_kernel<copy> (+ ew_fold_kernel) = ew_snapshot",
+             "verify": "ew_cksum_kernel<read-only> (+ ew_compare_kernel) = ew_verify",
+             "pack": "ew_segcopy_kernel = ew_pack", "unpack": "ew_segcopy_kernel = ew_unpack",
+             "unpack_snapshot": "ew_unpack_snap_kernel (+ ew_fold_tiles_kernel) = ew_unpack_snapshot"}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -36,15 +43,17 @@ def parse():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="7b_stage", choices=["tiny", "7b_stage", "13b_stage"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--unfused", action="store_true", help="run a6 (ew_unpack) and a7 (ew_snapshot) as separate passes")
-    ap.add_argument("--no-migration", action="store_true", help="skip the layer-migration comparison (Sec. 6.3)")
     ap.add_argument("--cpu-sample-units", type=int, default=8192)
+    ap.add_argument("--unfused", action="store_true",
+                    help="headline path runs a6 (ew_unpack) and a7 (ew_snapshot) separately")
+    ap.add_argument("--no-other-path", action="store_true", help="do not time the path that is not the headline")
+    ap.add_argument("--no-migration", action="store_true", help="skip the layer-migration comparison (Sec. 6.3)")
     return ap.parse_args()
 
 
 def read_traffic(kernel_key):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
-    (FETCH_SIZE / WRITE_SIZE runs); None when no summary for this workload exists."""
+    (FETCH_SIZE / WRITE_SIZE runs); None when no summary for this kernel and workload exists."""
     path = os.path.join(ROOT, "profiles", "pmc_traffic.txt")
     if not os.path.exists(path):
         return None
@@ -107,29 +116,24 @@ def main():
 
     numel = w.numel
     n_remote = stage_len
+    ck_old = 16 * sum(int(t.shape[0]) for a in A for t in sums[a])
     ck_new = 16 * sum(int(t.shape[0]) for a in A for t in nsums[a])
-    bytes_phase = {
-        "snapshot_old": sum(2 * n * 14 for n in old_len) + 16 * sum(int(t.shape[0]) for a in A for t in sums[a]),
-        "verify": sum(old_len[j] * 14 for j in w.failed),
-        "pack": 2 * 14 * n_remote,
-    }
-    launches = {"snapshot_old": 4 * w.old_dp, "verify": 4 * len(w.failed), "pack": 4}
-    if args.unfused:
-        bytes_phase["unpack"] = 2 * 14 * numel
-        bytes_phase["snapshot_new"] = sum(2 * n * 14 for n in new_len) + ck_new
-        launches.update({"unpack": 4, "snapshot_new": 4 * w.new_dp})
-    else:
-        bytes_phase["unpack_snapshot"] = 3 * 14 * numel + ck_new    # read once, written twice
-        launches["unpack_snapshot"] = 4
-    kernel_of = {"snapshot_old": "ew_cksum_slots_kernel<copy> (+ ew_fold_kernel) = ew_snapshot",
-                 "snapshot_new": "ew_cksum_slots_kernel<copy> (+ ew_fold_kernel) = ew_snapshot",
-                 "verify": "ew_cksum_kernel<read-only> (+ ew_compare_kernel) = ew_verify",
-                 "pack": "ew_segcopy_kernel = ew_pack", "unpack": "ew_segcopy_kernel = ew_unpack",
-                 "unpack_snapshot": "ew_unpack_snap_kernel (+ ew_fold_tiles_kernel) = ew_unpack_snapshot"}
-    step_bytes = sum(bytes_phase.values())
-    phases = list(bytes_phase)
 
-    def step(record):
+    def phase_table(unfused):
+        b = {"snapshot_old": sum(2 * n * 14 for n in old_len) + ck_old,
+             "verify": sum(old_len[j] * 14 for j in w.failed),
+             "pack": 2 * 14 * n_remote}
+        n = {"snapshot_old": 4 * w.old_dp, "verify": 4 * len(w.failed), "pack": 4}
+        if unfused:
+            b["unpack"] = 2 * 14 * numel
+            b["snapshot_new"] = sum(2 * x * 14 for x in new_len) + ck_new
+            n.update({"unpack": 4, "snapshot_new": 4 * w.new_dp})
+        else:
+            b["unpack_snapshot"] = 3 * 14 * numel + ck_new    # read once, written twice
+            n["unpack_snapshot"] = 4
+        return b, n
+
+    def step(unfused, record):
         ev = []
 
         def mark():
@@ -154,7 +158,7 @@ def main():
         for a in A:                                                                    # a4
             ew.ew_pack(plan, old_after[a], snap_used[a], stage[a], es[a], st)
         mark()
-        if args.unfused:
+        if unfused:
             for a in A:                                                                # a6
                 ew.ew_unpack(plan, stage[a], old_after[a], snap_used[a], new[a], es[a], st)
             mark()
@@ -167,28 +171,57 @@ def main():
         mark()
         return plan, t_plan, ev
 
-    plans = []
-    for _ in range(args.warmup):
-        p, _, _ = step(False)
-        plans.append(p)
-    torch.cuda.synchronize()
-    for p in plans:
-        p.close()
-    plans = []
+    def run_path(unfused, steps, warmup):
+        """W untimed steps, then exactly K timed steps between two device synchronisations."""
+        bytes_phase, launches = phase_table(unfused)
+        phases = list(bytes_phase)
+        plans = [step(unfused, False)[0] for _ in range(warmup)]
+        torch.cuda.synchronize()
+        for p in plans:
+            p.close()
+        plans, records = [], []
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            p, t_plan, ev = step(unfused, True)
+            plans.append(p)      # freed after the region: the kernels that use its tables are in flight
+            records.append((t_plan, ev))
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        for p in plans:
+            p.close()
+        assert int(n_bad.item()) == 0, "verification of an intact snapshot reported bad blocks"
+        phase_ms = {ph: sum(ev[i].elapsed_time(ev[i + 1]) for _, ev in records) / steps for i, ph in enumerate(phases)}
+        kernels = {}
+        for ph in phases:
+            if phase_ms[ph] > 0:
+                gbs = bytes_phase[ph] / phase_ms[ph] / 1e6
+                kernels[ph] = {"ms": round(phase_ms[ph], 4), "launches": launches[ph],
+                               "GB": round(bytes_phase[ph] / 1e9, 4), "GB/s": round(gbs, 1),
+                               "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4)}
+        # dominant kernel: the one whose launches take the most time in a step
+        groups = {}
+        for ph in phases:
+            g = groups.setdefault(KERNEL_OF[ph], [0.0, 0.0, 0])
+            g[0] += phase_ms[ph]
+            g[1] += bytes_phase[ph]
+            g[2] += launches[ph]
+        dom = max(groups, key=lambda k: groups[k][0])
+        d_ms, d_bytes, d_launches = groups[dom]
+        achieved = d_bytes / d_ms / 1e6
+        roofline = {"kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                    "traffic": read_traffic(f"{dom.split()[-1]}/{w.name}"),
+                    "bytes_per_launch": round(d_bytes / d_launches),
+                    "avg_launch_us": round(d_ms / d_launches * 1e3, 2)}
+        step_bytes = sum(bytes_phase.values())
+        return {"ms_per_step": elapsed / steps * 1e3, "value": step_bytes / (elapsed / steps) / 1e9,
+                "step_GB": step_bytes / 1e9, "plan_ms": sum(r[0] for r in records) / steps * 1e3,
+                "kernels": kernels, "roofline": roofline}
 
-    # ---------------- timed region: exactly K steps
-    records = []
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        p, t_plan, ev = step(True)
-        plans.append(p)          # freed after the region: the kernels that use its tables are in flight
-        records.append((t_plan, ev))
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    for p in plans:
-        p.close()
-    assert int(n_bad.item()) == 0, "verification of an intact snapshot reported bad blocks"
+    # ---------------- the timed region (inside run_path): exactly K steps of the headline path
+    head = run_path(args.unfused, args.steps, args.warmup)
+    other = None if args.no_other_path else run_path(not args.unfused, args.steps, 1)
 
     # yardstick (outside the timed region): the library's plain copy kernel on one fp32 rank shard,
     # i.e. what a copy with nothing else to do reaches on this GPU; these launches are also the
@@ -223,58 +256,30 @@ def main():
         rp.close()
     reshard_only_ms = sorted(reshard_runs)[len(reshard_runs) // 2]
 
-    ms_per_step = elapsed / args.steps * 1e3
-    value = step_bytes / (elapsed / args.steps) / 1e9
-    phase_ms = {ph: 0.0 for ph in phases}
-    for _, ev in records:
-        for i, ph in enumerate(phases):
-            phase_ms[ph] += ev[i].elapsed_time(ev[i + 1])
-    for ph in phases:
-        phase_ms[ph] /= args.steps
-    plan_ms = sum(r[0] for r in records) / args.steps * 1e3
-    kernels = {}
-    for ph in phases:
-        if phase_ms[ph] > 0:
-            gbs = bytes_phase[ph] / phase_ms[ph] / 1e6
-            kernels[ph] = {"ms": round(phase_ms[ph], 4), "launches": launches[ph], "GB": round(bytes_phase[ph] / 1e9, 4),
-                           "GB/s": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4)}
-    # dominant kernel: the one whose launches take the most time in a step (a2 and a7 are the same
-    # kernel when run unfused)
-    groups = {}
-    for ph in phases:
-        g = groups.setdefault(kernel_of[ph], [0.0, 0.0, 0])
-        g[0] += phase_ms[ph]
-        g[1] += bytes_phase[ph]
-        g[2] += launches[ph]
-    dom = max(groups, key=lambda k: groups[k][0])
-    d_ms, d_bytes, d_launches = groups[dom]
-    achieved = d_bytes / d_ms / 1e6
-    roofline = {
-        "kernel": dom, "bound": "hbm", "achieved": round(achieved, 1),
-        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-        "traffic": read_traffic(f"{dom.split()[-1]}/{w.name}"),
-        "bytes_per_launch": round(d_bytes / d_launches), "avg_launch_us": round(d_ms / d_launches * 1e3, 2),
-    }
-
+    names = {True: "unfused (ew_unpack, then ew_snapshot of the new shards)",
+             False: "fused (ew_unpack_snapshot also writes the new shards' snapshots and checksums)"}
     out = {
         "metric": "reshard+snapshot GB/s on one MI355X and % of HBM peak; time to reshard one stage",
-        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": round(head["value"], 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(head["ms_per_step"], 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u64", "data": "synthetic",
         "config": {"workload": w.name, "note": w.note, "numel": numel, "state_bytes": 14 * numel, "old_dp": w.old_dp,
                    "new_dp": w.new_dp, "failed": w.failed, "units": int(len(starts) - 1),
                    "remote_fraction": round(n_remote / numel, 4), "arrays": "bf16 P + fp32 W, M, V"},
-        "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
-        "path": "unfused (ew_unpack, then ew_snapshot of the new shards)" if args.unfused
-                else "fused (ew_unpack_snapshot also writes the new shards' snapshots and checksums)",
+        "frac_of_hbm_peak": round(head["value"] / HBM_PEAK_GBS, 4),
+        "path": names[args.unfused],
         "reshard_one_stage_ms": round(reshard_only_ms, 3),
         "reshard_useful_GBps": round(14 * numel / reshard_only_ms / 1e6, 1),
-        "plan_ms": round(plan_ms, 3),
-        "step_GB": round(step_bytes / 1e9, 3),
-        "kernels": kernels,
+        "plan_ms": round(head["plan_ms"], 3),
+        "step_GB": round(head["step_GB"], 3),
+        "kernels": head["kernels"],
         "plain_copy_GBps": round(copy_gbs, 1),
-        "roofline": roofline,
+        "roofline": head["roofline"],
     }
+    if other is not None:
+        out["other_path"] = {"path": names[not args.unfused], "ms_per_step": round(other["ms_per_step"], 3),
+                             "value": round(other["value"], 1), "step_GB": round(other["step_GB"], 3),
+                             "kernels": other["kernels"]}
 
     # ---------------- CPU baseline: the oracle as it stands, one core, on a bounded sample
     if not args.no_cpu_baseline:
@@ -304,16 +309,18 @@ def main():
             _ = [o_ck.block_checksums(h) for h in nsn]
             cpu_bytes += sum(2 * h.nbytes for h in new_h)
         cpu_s = time.perf_counter() - c0
-        # pack+unpack traffic of the sample under the same accounting as the GPU figure
+        # pack+unpack traffic of the sample under the byte accounting of the unfused GPU path
         p_s = ew.ew_plan_bounds(w.old_dp, w.new_dp, w.alive_mask, s_starts.astype(np.uint64))
         cpu_bytes += 2 * 14 * (s_numel + p_s.stage_len)
         p_s.close()
         out["cpu_baseline"] = {
             "value": round(cpu_bytes / cpu_s / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
             "sample": f"first {n_units} of {len(starts) - 1} units of {w.name} ({s_numel} elements, all four arrays): "
-                      f"numpy oracle snapshot+checksum, verify, reconstruct+slice, snapshot+checksum of the result; "
-                      f"{cpu_s:.1f} s on one host core",
+                      f"numpy oracle snapshot+checksum, verify, reconstruct+slice, snapshot+checksum of the result, "
+                      f"bytes counted as for the unfused GPU path; {cpu_s:.1f} s on one host core",
         }
+        del host
+
     # ---------------- layer migration, contiguous vs interleaved assignment (Sec. 6.3); not part of `value`
     if not args.no_migration and w.name != "tiny":
         del old, snap, sums, stage, new, nsnap, nsums, got, old_after, snap_used
@@ -326,7 +333,6 @@ def migration_compare(ew, configs, synth, torch, st, dev):
     """Moves one Llama-7B-shaped layer between two 4-layer stages at DP 8 under both ZeRO assignments,
     all four state arrays, and reports what crosses between ranks (the arena) and how long the send
     side (ew_pack) and the whole move (ew_pack + ew_unpack) take on this GPU."""
-    import numpy as np
     D = 8
     wl = configs.Workload("migrate", 9, configs.stage_tensors(4096, 11008, 4), D, D, 0xFF, 262144, snap_to_tensors=True)
     starts = wl.unit_starts()
