@@ -46,7 +46,8 @@ enum {
                               where data is needed, plan not uploaded)                          */
   EW_EUNRECOVERABLE = -2,  /* no survivor, or a failed rank whose ring predecessor failed too */
   EW_ENOMEM = -3,          /* host or device allocation failed                                 */
-  EW_EHIP = -4             /* HIP runtime error; text of the last one via ew_strerror(EW_EHIP) */
+  EW_EHIP = -4,            /* HIP runtime error; text of the last one via ew_strerror(EW_EHIP) */
+  EW_EINFEASIBLE = -5      /* ew_partition_layers: no partition fits the stages' memory caps   */
 };
 
 typedef struct ew_plan_s ew_plan_t; /* opaque */
@@ -110,6 +111,20 @@ int ew_plan_bounds(uint32_t old_dp, uint32_t new_dp, uint64_t alive_mask, uint64
 #define EW_ASSIGN_CONTIGUOUS 1u
 int ew_plan_migrate(uint32_t assignment, uint32_t dp, uint64_t n_src_units, const uint64_t *src_unit_starts,
                     uint64_t n_dst_units, const uint64_t *dst_unit_starts, uint64_t n_move, ew_plan_t **out);
+
+/* ---- Which layers sit on which stage: minimax layer partition (Sec. 4.2, Eq. 2-3, Alg. 1) ------
+ * Cuts layers 0..n_layers-1 into n_stages non-empty contiguous blocks, block p on stage p, so that
+ * every block's memory fits its stage and the largest per-stage mini-step time is minimal.  The
+ * result says which boundary layers have to move between adjacent stages (ew_plan_migrate).
+ * t:   host [n_stages][n_layers][n_layers], t[p][a][b] = mini-step time of stage p hosting layers
+ *      a..b (entries with a > b are ignored);
+ * mem: host [n_layers][n_layers], mem[a][b] = memory of layers a..b on one stage; cap: host [n_stages].
+ * out_bounds: host [n_stages-1], out_bounds[p] = number of layers on stages 0..p (stage p hosts
+ * layers out_bounds[p-1] .. out_bounds[p]-1); *out_cost = the optimal worst-stage time.  Among
+ * optimal partitions the one found by scanning split points upward is returned.
+ * EW_EINFEASIBLE if no partition fits; EW_EINVAL for zero sizes, more stages than layers, NULLs. */
+int ew_partition_layers(uint32_t n_layers, uint32_t n_stages, const double *t, const double *mem,
+                        const double *cap, uint32_t *out_bounds, double *out_cost);
 
 /* Frees host and device tables.  Work enqueued with this plan must have completed. */
 void ew_plan_free(ew_plan_t *plan);

@@ -13,7 +13,7 @@ import os
 
 import numpy as np
 
-EW_OK, EW_EINVAL, EW_EUNRECOVERABLE, EW_ENOMEM, EW_EHIP = 0, -1, -2, -3, -4
+EW_OK, EW_EINVAL, EW_EUNRECOVERABLE, EW_ENOMEM, EW_EHIP, EW_EINFEASIBLE = 0, -1, -2, -3, -4, -5
 EW_MAX_DP = 64
 EW_GRANULE = 8
 EW_CKSUM_BLOCK = 1 << 20
@@ -42,6 +42,8 @@ _SIGNATURES = {
     "ew_plan_bounds": (C.c_int, [C.c_uint32, C.c_uint32, C.c_uint64, C.c_uint64, C.c_void_p, C.POINTER(C.c_void_p)]),
     "ew_plan_migrate": (C.c_int, [C.c_uint32, C.c_uint32, C.c_uint64, C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64,
                                   C.POINTER(C.c_void_p)]),
+    "ew_partition_layers": (C.c_int, [C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.POINTER(C.c_double)]),
     "ew_plan_free": (None, [C.c_void_p]),
     "ew_plan_numel": (C.c_uint64, [C.c_void_p]),
     "ew_plan_old_dp": (C.c_uint32, [C.c_void_p]),
@@ -232,6 +234,22 @@ def ew_plan_migrate(assignment: int, dp: int, src_unit_starts, dst_unit_starts, 
     _check(lib().ew_plan_migrate(assignment, dp, len(src) - 1, src.ctypes.data, len(dst) - 1, dst.ctypes.data, n_move,
                                  C.byref(out)), "ew_plan_migrate")
     return Plan(out.value)
+
+
+def ew_partition_layers(t, mem, cap):
+    """t[p][a][b], mem[a][b], cap[p] (array-likes).  Returns (cost, bounds) with bounds[p] = number of
+    layers on stages 0..p; raises EwError(EW_EINFEASIBLE) if nothing fits."""
+    t = np.ascontiguousarray(t, dtype=np.float64)
+    mem = np.ascontiguousarray(mem, dtype=np.float64)
+    cap = np.ascontiguousarray(cap, dtype=np.float64)
+    if t.ndim != 3 or t.shape[1] != t.shape[2] or mem.shape != t.shape[1:] or cap.shape != (t.shape[0],):
+        raise ValueError("expected t[P][L][L], mem[L][L], cap[P]")
+    P, L = t.shape[0], t.shape[1]
+    bounds = np.zeros(max(P - 1, 1), dtype=np.uint32)
+    cost = C.c_double()
+    _check(lib().ew_partition_layers(L, P, t.ctypes.data, mem.ctypes.data, cap.ctypes.data, bounds.ctypes.data,
+                                     C.byref(cost)), "ew_partition_layers")
+    return cost.value, [int(x) for x in bounds[:P - 1]]
 
 
 def ew_plan_upload(plan: Plan, tile_elems: int = 0, stream=None):

@@ -984,6 +984,7 @@ const char *ew_strerror(int code) {
       return "unrecoverable: no survivor, or a failed rank's snapshot holder (ring predecessor) failed too";
     case EW_ENOMEM: return "out of memory";
     case EW_EHIP: return g_hip_error.c_str();
+    case EW_EINFEASIBLE: return "infeasible: no layer partition fits the stages' memory caps";
     default: return "unknown error code";
   }
 }
