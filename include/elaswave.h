@@ -230,6 +230,38 @@ int ew_verify(const void *buf, uint64_t nbytes, const ew_cksum_t *expect, ew_cks
               uint64_t *n_bad, uint64_t *bad_blocks, ew_cksum_t *diffs, uint64_t cap,
               void *stream);
 
+/* ---- Gradient-shipping snapshot (Sec. 5.1, Fig. 6) --------------------------------------------
+ * The paper keeps worker i's snapshot of worker (i+1)'s optimizer partition current without copying
+ * the Adam state every step: worker i+1 ships the GRADIENT shard of its partition (device to device,
+ * then device to host on worker i) and worker i's host CPU replays the optimizer update on the
+ * snapshot in host memory.  The replay reproduces the owner's update bit for bit because both run
+ * the same sequence of single fp32 operations (no fused multiply-add, correctly rounded divide and
+ * square root):  m <- beta1*m + (1-beta1)*g;  v <- beta2*v + (1-beta2)*(g*g);
+ * w <- w - lr*((m*bias1)/(sqrt(v*bias2) + eps) + weight_decay*w);  p <- bf16(w), nearest even. */
+typedef struct {
+  float lr, beta1, beta2;
+  float omb1, omb2;   /* 1-beta1, 1-beta2, rounded once from float64 */
+  float eps, wd;
+  float bias1, bias2; /* 1/(1-beta1^t), 1/(1-beta2^t), rounded once from float64 */
+} ew_adam_t;
+/* Fills *out for optimizer step `step` (1-based).  EW_EINVAL for step 0 or betas outside [0, 1). */
+int ew_adam_hyper(float lr, float beta1, float beta2, float eps, float weight_decay, uint64_t step, ew_adam_t *out);
+/* The owner's step on its live shard: p_bf16, w, m, v (device, n elements each; updated in place),
+ * grad (device, n elements of grad_elem_size 4 = fp32 or 2 = bf16).  Enqueued on `stream`. */
+int ew_adam_step(void *p_bf16, float *w, float *m, float *v, const void *grad, uint32_t grad_elem_size, uint64_t n,
+                 const ew_adam_t *h, void *stream);
+/* The same update on a snapshot in HOST memory (all pointers host), split over n_threads host
+ * threads (0 = all hardware threads).  Synchronous.  This runs on the CPU by the paper's design; it
+ * is not a fallback for anything. */
+int ew_adam_replay_host(void *p_bf16, float *w, float *m, float *v, const void *grad, uint32_t grad_elem_size,
+                        uint64_t n, const ew_adam_t *h, uint32_t n_threads);
+/* Ships a gradient shard: grad_dev -> peer_dev (device to device; NULL skips the hop) -> host_buf
+ * (device to host; pinned host memory keeps it asynchronous; NULL skips it), on `stream`. */
+int ew_grad_ship(const void *grad_dev, void *peer_dev, void *host_buf, uint64_t nbytes, void *stream);
+/* Block checksums (as ew_snapshot's) of a HOST buffer into cksums (host), over n_threads threads:
+ * upload them and run ew_verify on the live device shard to check a host snapshot against it. */
+int ew_checksum_host(const void *buf, uint64_t nbytes, ew_cksum_t *cksums, uint32_t n_threads);
+
 /* Plain device copy dst[0..nbytes) = src[0..nbytes) with the access pattern of the copy tiles
  * (128-bit vectors, 4 KiB per workgroup) and nothing else: the yardstick that benchmarks quote
  * the other kernels against and that profiler byte counters are calibrated with.  Not part of

@@ -70,6 +70,13 @@ _SIGNATURES = {
     "ew_snapshot": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]),
     "ew_verify": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                             C.c_uint64, C.c_void_p]),
+    "ew_adam_hyper": (C.c_int, [C.c_float, C.c_float, C.c_float, C.c_float, C.c_float, C.c_uint64, C.c_void_p]),
+    "ew_adam_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint64,
+                               C.c_void_p, C.c_void_p]),
+    "ew_adam_replay_host": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32,
+                                      C.c_uint64, C.c_void_p, C.c_uint32]),
+    "ew_grad_ship": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]),
+    "ew_checksum_host": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint32]),
     "ew_memcpy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]),
     "ew_set_param": (C.c_int, [C.c_char_p, C.c_int64]),
     "ew_get_param": (C.c_int64, [C.c_char_p]),
@@ -110,6 +117,8 @@ def _ptr(x) -> int:
 
 def _nbytes(x):
     """Size of a tensor-like buffer in bytes, or None for a raw address."""
+    if isinstance(x, np.ndarray):
+        return int(x.nbytes)
     if hasattr(x, "numel") and hasattr(x, "element_size"):
         return int(x.numel()) * int(x.element_size())
     return None
@@ -331,6 +340,69 @@ def ew_verify(buf, nbytes: int, expect, got, n_bad, bad_blocks, diffs, cap: int,
             raise ValueError(f"{name} holds {n} bytes, call needs {need}")
     _check(lib().ew_verify(_ptr(buf), nbytes, _ptr(expect), _ptr(got), _ptr(n_bad), _ptr(bad_blocks), _ptr(diffs),
                            cap, _stream(stream)), "ew_verify")
+
+
+class AdamHyper(C.Structure):
+    """ew_adam_t: the nine fp32 scalars of one optimizer step."""
+    _fields_ = [(n, C.c_float) for n in ("lr", "beta1", "beta2", "omb1", "omb2", "eps", "wd", "bias1", "bias2")]
+
+
+def ew_adam_hyper(lr, beta1, beta2, eps, weight_decay, step: int) -> AdamHyper:
+    h = AdamHyper()
+    _check(lib().ew_adam_hyper(lr, beta1, beta2, eps, weight_decay, step, C.byref(h)), "ew_adam_hyper")
+    return h
+
+
+def _check_len(name, buf, need):
+    n = _nbytes(buf)
+    if n is not None and n < need:
+        raise ValueError(f"{name} holds {n} bytes, call needs {need}")
+
+
+def ew_adam_step(p, w, m, v, grad, grad_elem_size: int, n: int, h: AdamHyper, stream=None):
+    """Device buffers (tensors or raw addresses)."""
+    for name, b, need in (("p", p, 2 * n), ("w", w, 4 * n), ("m", m, 4 * n), ("v", v, 4 * n),
+                          ("grad", grad, grad_elem_size * n)):
+        _check_len(name, b, need)
+    _check(lib().ew_adam_step(_ptr(p), _ptr(w), _ptr(m), _ptr(v), _ptr(grad), grad_elem_size, n, C.byref(h),
+                              _stream(stream)), "ew_adam_step")
+
+
+def ew_adam_replay_host(p, w, m, v, grad, grad_elem_size: int, n: int, h: AdamHyper, n_threads: int = 0):
+    """Host buffers: CPU tensors or numpy arrays (updated in place)."""
+    for name, b, need in (("p", p, 2 * n), ("w", w, 4 * n), ("m", m, 4 * n), ("v", v, 4 * n),
+                          ("grad", grad, grad_elem_size * n)):
+        _check_len(name, b, need)
+    _check(lib().ew_adam_replay_host(_host_ptr(p), _host_ptr(w), _host_ptr(m), _host_ptr(v), _host_ptr(grad),
+                                     grad_elem_size, n, C.byref(h), n_threads), "ew_adam_replay_host")
+
+
+def ew_grad_ship(grad_dev, peer_dev, host_buf, nbytes: int, stream=None):
+    for name, b in (("grad", grad_dev), ("peer buffer", peer_dev), ("host buffer", host_buf)):
+        if b is not None:
+            _check_len(name, b, nbytes)
+    _check(lib().ew_grad_ship(_ptr(grad_dev), _ptr(peer_dev), _host_ptr(host_buf) if host_buf is not None else 0,
+                              nbytes, _stream(stream)), "ew_grad_ship")
+
+
+def ew_checksum_host(buf, nbytes: int, n_threads: int = 0) -> np.ndarray:
+    """Block checksums of a host buffer as a CKSUM_DTYPE array."""
+    _check_len("buf", buf, nbytes)
+    out = np.zeros(num_blocks(nbytes), CKSUM_DTYPE)
+    _check(lib().ew_checksum_host(_host_ptr(buf), nbytes, out.ctypes.data, n_threads), "ew_checksum_host")
+    return out
+
+
+def _host_ptr(x) -> int:
+    if x is None:
+        return 0
+    if isinstance(x, np.ndarray):
+        return int(x.ctypes.data)
+    if hasattr(x, "data_ptr"):
+        if getattr(x, "is_cuda", False):
+            raise ValueError("expected a host buffer, got a device tensor")
+        return int(x.data_ptr())
+    return int(x)
 
 
 def ew_memcpy(src, dst, nbytes: int, stream=None):

@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libelaswave.so")
 SOURCES = [os.path.join(HERE, "csrc", "plan.cpp"), os.path.join(HERE, "csrc", "partition.cpp"),
-           os.path.join(HERE, "csrc", "kernels.hip")]
+           os.path.join(HERE, "csrc", "kernels.hip"), os.path.join(HERE, "csrc", "adam.hip")]
 
 
 def hipcc_path() -> str:
