@@ -278,6 +278,42 @@ def main():
         "plain_copy_GBps": round(copy_gbs, 1),
         "roofline": head["roofline"],
     }
+    if w.name == "tiny":
+        # cache-resident and launch bound: read these as latencies, not as fractions of HBM peak.  The
+        # device part of a step (a2..a7, ~45 launches) replayed from a HIP graph vs issued call by call.
+        side = torch.cuda.Stream()
+        gplan = ew.ew_plan_bounds(w.old_dp, w.new_dp, w.alive_mask, starts)
+        ew.ew_plan_upload(gplan, 0, side.cuda_stream)
+
+        def device_part(s):
+            for a in A:
+                for j in range(w.old_dp):
+                    ew.ew_snapshot(old[a][j], snap[a][j], old_len[j] * es[a], sums[a][j], s)
+            for a in A:
+                for j in w.failed:
+                    ew.ew_verify(snap[a][j], old_len[j] * es[a], sums[a][j], got[a][j], n_bad, bad, diffs, 16, s)
+            for a in A:
+                ew.ew_pack(gplan, old_after[a], snap_used[a], stage[a], es[a], s)
+                ew.ew_unpack_snapshot(gplan, stage[a], old_after[a], snap_used[a], new[a], nsnap[a], nsums[a], es[a], s)
+
+        with torch.cuda.stream(side):
+            device_part(side.cuda_stream)
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            device_part(torch.cuda.current_stream().cuda_stream)
+        lat = {}
+        for name, fn in (("eager", lambda: device_part(st)), ("graph_replay", graph.replay)):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(50):
+                fn()
+            torch.cuda.synchronize()
+            lat[name + "_us"] = round((time.perf_counter() - t0) / 50 * 1e6, 1)
+        out["tiny_step_latency"] = lat
+        gplan.close()
     if other is not None:
         out["other_path"] = {"path": names[not args.unfused], "ms_per_step": round(other["ms_per_step"], 3),
                              "value": round(other["value"], 1), "step_GB": round(other["step_GB"], 3),
