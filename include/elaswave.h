@@ -202,8 +202,9 @@ int ew_unpack(const ew_plan_t *plan, const void *stage, const void *const *old_s
  * read once: it is stored to the new shard and to its snapshot copy and folded into the checksum
  * of the new shard's 1 MiB block it lands in.  new_snapshots, new_cksums: host arrays of new_dp
  * device pointers (buffers of new_len[k]*elem_size bytes / ceil(that / 2^20) records, records
- * overwritten).  Uses the library's scratch array like ew_snapshot: EW_ENOMEM if more than 4
- * streams of a device already use it; EW_EINVAL if the plan was uploaded with tiles above 1 MiB. */
+ * overwritten).  Uses the library's scratch array like ew_snapshot: EW_ENOMEM only for a stream
+ * under graph capture that owns no scratch region yet (run the call once on it before capturing);
+ * EW_EINVAL if the plan was uploaded with tiles above 1 MiB. */
 int ew_unpack_snapshot(const ew_plan_t *plan, const void *stage, const void *const *old_shards,
                        const void *const *snapshots, void *const *new_shards, void *const *new_snapshots,
                        ew_cksum_t *const *new_cksums, uint32_t elem_size, void *stream);
@@ -213,10 +214,12 @@ int ew_unpack_snapshot(const ew_plan_t *plan, const void *stage, const void *con
  * 64-bit words of bytes [b*2^20, min((b+1)*2^20, nbytes)), a trailing partial word being
  * zero-padded.  src, dst, cksums: device; cksums has ceil(nbytes / 2^20) records and is
  * overwritten.  src and dst must not overlap.  nbytes = 0 is a no-op.
- * Never allocates: per-workgroup partial checksums go through a fixed scratch array inside the
- * library (128 MiB per device), one region per stream for the first 4 streams that call
- * ew_snapshot / ew_verify on a device; calls on further streams, and calls with buffers that are
- * not 16-byte aligned, use a slower kernel that needs no scratch.  Calls may be issued from
+ * Never allocates device memory: per-workgroup partial checksums go through a fixed scratch array
+ * inside the library (128 MiB per device, 4 regions).  A stream keeps the region it used last; when
+ * more than 4 streams take turns, the least recently used region changes hands and the new stream
+ * is made to wait (on the device, not the host) for that region's last use.  Buffers that are not
+ * 16-byte aligned, and a stream under graph capture that owns no region yet (run the calls once on
+ * it before capturing), use a slower kernel that needs no scratch.  Calls may be issued from
  * several host threads. */
 int ew_snapshot(const void *src, void *dst, uint64_t nbytes, ew_cksum_t *cksums, void *stream);
 
@@ -270,7 +273,7 @@ int ew_checksum_host(const void *buf, uint64_t nbytes, ew_cksum_t *cksums, uint3
 int ew_memcpy(const void *src, void *dst, uint64_t nbytes, void *stream);
 
 /* Launch-shape knobs for benchmarking sweeps (process-wide, not thread-safe; defaults are the
- * tuned ones).  Names: "tile_bytes", "tile_elems", "tile_align_bytes", "copy_wgs_per_cu", "cksum_sub_bytes",
+ * tuned ones).  Names: "tile_bytes", "tile_elems", "tile_align_bytes", "cksum_sub_bytes",
  * "cksum_wgs_per_cu", "cksum_mode" (-1 = default: slot kernel + fold for ew_snapshot, atomic kernel
  * for ew_verify; 0 / 1 force the slot / atomic kernel for both).
  * Returns EW_EINVAL for an unknown name or an out-of-range value. */

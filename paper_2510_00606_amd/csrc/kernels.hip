@@ -20,6 +20,7 @@
 namespace {
 
 using ew::RunT;
+using ew::TableRef;
 using ew::TileT;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -52,7 +53,6 @@ int hip_fail(hipError_t e, const char *what) {
   } while (0)
 
 // process-wide launch-shape knobs (see ew_set_param)
-int64_t g_copy_wgs_per_cu = 0;     // 0 = one workgroup per tile, else persistent grid = CUs * this
 int64_t g_cksum_sub_bytes = 65536; // bytes of a checksum block handled by one workgroup pass
 int64_t g_cksum_wgs_per_cu = 0;    // 0 = one workgroup per sub-block, else persistent grid
 int64_t g_cksum_mode = -1;         // -1 = slot kernel + fold for snapshot, atomic kernel for verify;
@@ -103,11 +103,12 @@ struct CopyTabs {
 };
 
 template <int ES>
-__global__ __launch_bounds__(kThreads) void ew_segcopy_kernel(const RunT *__restrict__ runs, uint32_t nruns,
-                                                              const TileT *__restrict__ templ,
-                                                              uint64_t ntiles, CopyTabs tabs) {
-  for (uint64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
-    const ew::TileRef tl = ew::decode_tile(runs, nruns, templ, t);
+__global__ __launch_bounds__(kThreads) void ew_segcopy_kernel(TableRef table, CopyTabs tabs) {
+  // No loop over tiles: every table load then precedes every store of the workgroup, which lets the
+  // compiler keep the decode on the scalar unit (a persistent loop forces vector loads of the
+  // tables, since a store might alias them: 3.9 instead of 6.2 TB/s).
+  {
+    const ew::TileRef tl = ew::decode_tile(table, blockIdx.x);
     const char *s = tabs.src[tl.src_buf] + tl.src_off * ES;
     char *d = tabs.dst[tl.dst_buf] + tl.dst_off * ES;
     const uint32_t nbytes = tl.len * ES;
@@ -401,14 +402,12 @@ __device__ __forceinline__ void block_fold(uint64_t &sum, uint64_t &xr, uint64_t
 }
 
 template <int ES>
-__global__ __launch_bounds__(kThreads) void ew_unpack_snap_kernel(const RunT *__restrict__ runs, uint32_t nruns,
-                                                                  const TileT *__restrict__ templ,
-                                                                  uint64_t tile_base, CopyTabs tabs, SnapTabs st,
-                                                                  ew_cksum_t *__restrict__ slots) {
+__global__ __launch_bounds__(kThreads) void ew_unpack_snap_kernel(TableRef table, uint64_t tile_base, CopyTabs tabs,
+                                                                  SnapTabs st, ew_cksum_t *__restrict__ slots) {
   __shared__ uint64_t lds_sum[kThreads / 64], lds_xor[kThreads / 64];
   __shared__ uint64_t lds_sum_hi[kThreads / 64], lds_xor_hi[kThreads / 64];
   typedef typename std::conditional<ES == 2, uint16_t, uint32_t>::type elem_t;
-  const ew::TileRef tl = ew::decode_tile(runs, nruns, templ, tile_base + blockIdx.x);
+  const ew::TileRef tl = ew::decode_tile(table, tile_base + blockIdx.x);
   const char *s = tabs.src[tl.src_buf] + tl.src_off * ES;
   const uint64_t dbyte = tl.dst_off * ES;  // byte offset inside the new shard
   char *d = tabs.dst[tl.dst_buf] + dbyte;
@@ -486,9 +485,7 @@ __global__ __launch_bounds__(kThreads) void ew_unpack_snap_kernel(const RunT *__
 // Lane g adds the slots of tiles [g*per_lane, (g+1)*per_lane) of the pass to the records, one
 // pair of atomics per run of tiles that share (new rank, block): tiles of a segment are adjacent.
 template <int ES>
-__global__ __launch_bounds__(kThreads) void ew_fold_tiles_kernel(const RunT *__restrict__ runs, uint32_t nruns,
-                                                                 const TileT *__restrict__ templ,
-                                                                 uint64_t tile_base, uint64_t ntiles,
+__global__ __launch_bounds__(kThreads) void ew_fold_tiles_kernel(TableRef table, uint64_t tile_base, uint64_t ntiles,
                                                                  uint32_t per_lane, SnapTabs st,
                                                                  const ew_cksum_t *__restrict__ slots) {
   const uint64_t g = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
@@ -499,7 +496,7 @@ __global__ __launch_bounds__(kThreads) void ew_fold_tiles_kernel(const RunT *__r
   uint64_t key_blk = 0, sum = 0, xr = 0;
   bool open = false;
   for (; i < end; ++i) {
-    const ew::TileRef tl = ew::decode_tile(runs, nruns, templ, tile_base + i);
+    const ew::TileRef tl = ew::decode_tile(table, tile_base + i);
     const uint64_t blk = (tl.dst_off * ES) >> 20;
     if (open && (tl.dst_buf != key_rank || blk != key_blk)) {
       ew_cksum_t *rec = st.rec[key_rank] + key_blk;
@@ -599,19 +596,11 @@ void release_tables(ew_plan_t *plan) {
 
 int launch_segcopy(const ew::TileTable &tt, const CopyTabs &tabs, uint32_t elem_size, hipStream_t stream) {
   if (tt.ntiles == 0) return EW_OK;
-  uint64_t grid = tt.ntiles;
-  if (g_copy_wgs_per_cu > 0) {
-    const uint64_t cap = (uint64_t)num_cus() * (uint64_t)g_copy_wgs_per_cu;
-    if (grid > cap) grid = cap;
-  }
-  if (grid > 0x7fffffffull) grid = 0x7fffffffull;
-  const uint32_t nruns = (uint32_t)tt.runs.size();
+  const uint32_t grid = (uint32_t)tt.ntiles;  // ew_plan_upload refuses tables above 2^31-1 tiles
   if (elem_size == 2)
-    hipLaunchKernelGGL(ew_segcopy_kernel<2>, dim3((uint32_t)grid), dim3(kThreads), 0, stream, tt.d_runs, nruns,
-                       tt.d_templ, tt.ntiles, tabs);
+    hipLaunchKernelGGL(ew_segcopy_kernel<2>, dim3(grid), dim3(kThreads), 0, stream, tt.dev, tabs);
   else
-    hipLaunchKernelGGL(ew_segcopy_kernel<4>, dim3((uint32_t)grid), dim3(kThreads), 0, stream, tt.d_runs, nruns,
-                       tt.d_templ, tt.ntiles, tabs);
+    hipLaunchKernelGGL(ew_segcopy_kernel<4>, dim3(grid), dim3(kThreads), 0, stream, tt.dev, tabs);
   EW_HIP(hipGetLastError());
   return EW_OK;
 }
@@ -627,25 +616,46 @@ int launch_zero(void *p, uint64_t nbytes, hipStream_t stream) {
 }
 
 // ---- scratch for the per-workgroup checksum slots --------------------------------------------
-// A fixed device array, so taking a snapshot never allocates.  It is cut into regions, one per
-// stream that uses the library (first come, first served); a call on a stream that finds no free
-// region uses the atomic kernel instead, which needs no scratch.  One region (32 MiB) covers
-// 8 GiB of input per pass; longer buffers are processed in several passes on the stream.
+// A fixed device array, so taking a snapshot never allocates.  It is cut into regions; a stream
+// keeps the region it used last.  When a stream without a region asks for one and all are taken,
+// the least recently used region changes hands, and the new owner's stream is first made to wait
+// (hipStreamWaitEvent, no host blocking) for the event recorded after the region's last use, so
+// two streams never touch a region at once.  A stream under graph capture can only use a region it
+// already owns (its warm-up run claims one); otherwise ew_snapshot falls back to the atomic kernel,
+// which needs no scratch.  One region (32 MiB) covers 8 GiB of input per pass; longer buffers are
+// processed in several passes on the stream.
 constexpr uint32_t kRegions = 4;
 constexpr uint64_t kRegionSlots = 1ull << 21;                       // 32 MiB of 16-byte slots
 constexpr uint64_t kPassBytes = kRegionSlots * 4096;                 // 8 GiB
 __device__ __align__(256) ew_cksum_t g_slot_scratch[kRegions * kRegionSlots];
 
+struct Region {
+  hipStream_t owner = nullptr;
+  bool taken = false;
+  hipEvent_t done = nullptr;   // recorded on the owner's stream after each use
+  bool recorded = false;
+  uint64_t last_use = 0;
+};
 struct ScratchState {
   std::mutex mu;
-  ew_cksum_t *base[64] = {nullptr};         // per device: address of that device's copy of the array
-  hipStream_t owner[64][kRegions];
-  uint32_t used[64] = {0};
+  ew_cksum_t *base[64] = {nullptr};  // per device: address of that device's copy of the array
+  Region region[64][kRegions];
+  uint64_t clock = 0;
 };
 ScratchState g_scratch;
 
-// Caller holds g_scratch.mu.  Returns the region's device address, or nullptr (no region / error).
-ew_cksum_t *region_for(hipStream_t stream) {
+bool stream_is_capturing(hipStream_t stream) {
+  hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(stream, &st) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  return st != hipStreamCaptureStatusNone;
+}
+
+// Caller holds g_scratch.mu.  Returns the region's device address (and the region through *out), or
+// nullptr when none can be had.
+ew_cksum_t *acquire_region(hipStream_t stream, Region **out) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
   if (!g_scratch.base[dev]) {
@@ -656,12 +666,39 @@ ew_cksum_t *region_for(hipStream_t stream) {
     }
     g_scratch.base[dev] = (ew_cksum_t *)p;
   }
-  for (uint32_t r = 0; r < g_scratch.used[dev]; ++r)
-    if (g_scratch.owner[dev][r] == stream) return g_scratch.base[dev] + (uint64_t)r * kRegionSlots;
-  if (g_scratch.used[dev] == kRegions) return nullptr;
-  const uint32_t r = g_scratch.used[dev]++;
-  g_scratch.owner[dev][r] = stream;
-  return g_scratch.base[dev] + (uint64_t)r * kRegionSlots;
+  Region *reg = g_scratch.region[dev];
+  int pick = -1;
+  for (uint32_t r = 0; r < kRegions && pick < 0; ++r)
+    if (reg[r].taken && reg[r].owner == stream) pick = (int)r;
+  for (uint32_t r = 0; r < kRegions && pick < 0; ++r)
+    if (!reg[r].taken) pick = (int)r;
+  if (pick < 0) {
+    if (stream_is_capturing(stream)) return nullptr;  // cannot order a capture after outside work
+    pick = 0;
+    for (uint32_t r = 1; r < kRegions; ++r)
+      if (reg[r].last_use < reg[pick].last_use) pick = (int)r;
+    if (reg[pick].recorded && hipStreamWaitEvent(stream, reg[pick].done, 0) != hipSuccess) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+  }
+  reg[pick].taken = true;
+  reg[pick].owner = stream;
+  *out = &reg[pick];
+  return g_scratch.base[dev] + (uint64_t)pick * kRegionSlots;
+}
+
+// Caller holds g_scratch.mu; called after the last kernel of a call has been enqueued.
+void release_region(Region *r, hipStream_t stream) {
+  r->last_use = ++g_scratch.clock;
+  if (stream_is_capturing(stream)) return;  // the graph's own ordering covers replays
+  if (!r->done && hipEventCreateWithFlags(&r->done, hipEventDisableTiming) != hipSuccess) {
+    (void)hipGetLastError();
+    r->done = nullptr;
+    return;
+  }
+  r->recorded = hipEventRecord(r->done, stream) == hipSuccess;
+  if (!r->recorded) (void)hipGetLastError();
 }
 
 template <bool COPY>
@@ -699,7 +736,8 @@ int launch_cksum(const void *src, void *dst, uint64_t nbytes, ew_cksum_t *out, h
   if (!aligned || mode != 0) return launch_cksum_atomic<COPY>(src, dst, nbytes, out, stream);
   // the (slot kernel, fold kernel) pairs of one call must reach the stream back to back
   std::lock_guard<std::mutex> lock(g_scratch.mu);
-  ew_cksum_t *slots = region_for(stream);
+  Region *region = nullptr;
+  ew_cksum_t *slots = acquire_region(stream, &region);
   if (!slots) return launch_cksum_atomic<COPY>(src, dst, nbytes, out, stream);
   for (uint64_t off = 0; off < nbytes; off += kPassBytes) {
     const uint64_t n = nbytes - off < kPassBytes ? nbytes - off : kPassBytes;
@@ -715,6 +753,7 @@ int launch_cksum(const void *src, void *dst, uint64_t nbytes, ew_cksum_t *out, h
                        out + off / EW_CKSUM_BLOCK);
     EW_HIP(hipGetLastError());
   }
+  release_region(region, stream);
   return EW_OK;
 }
 
@@ -774,7 +813,8 @@ int ew_plan_upload(ew_plan_t *plan, uint32_t tile_elems, void *stream) {
           release_tables(plan);
           return EW_EINVAL;
         }
-        bytes += tt.runs.size() * sizeof(RunT) + tt.templ.size() * sizeof(TileT);
+        bytes += tt.runs.size() * sizeof(RunT) + tt.templ.size() * sizeof(TileT) +
+                 ((tt.coarse.size() * sizeof(uint32_t) + 15) & ~(size_t)15);
       }
     }
   } catch (const std::bad_alloc &) {
@@ -793,12 +833,19 @@ int ew_plan_upload(ew_plan_t *plan, uint32_t tile_elems, void *stream) {
       for (int e = 0; e < 2; ++e) {  // templates (48 B records) first keeps everything 16-byte aligned
         ew::TileTable &tt = plan->tables[w][e];
         const size_t tb = tt.templ.size() * sizeof(TileT), rb = tt.runs.size() * sizeof(RunT);
+        const size_t cb = (tt.coarse.size() * sizeof(uint32_t) + 15) & ~(size_t)15;
+        tt.dev.nruns = (uint32_t)tt.runs.size();
+        tt.dev.shift = tt.shift;
         std::memcpy(h + off, tt.templ.data(), tb);
-        tt.d_templ = (const TileT *)(d + off);
+        tt.dev.templ = (const TileT *)(d + off);
         off += tb;
         std::memcpy(h + off, tt.runs.data(), rb);
-        tt.d_runs = (const RunT *)(d + off);
+        tt.dev.runs = (const RunT *)(d + off);
         off += rb;
+        std::memset(h + off, 0, cb);
+        std::memcpy(h + off, tt.coarse.data(), tt.coarse.size() * sizeof(uint32_t));
+        tt.dev.coarse = (const uint32_t *)(d + off);
+        off += cb;
       }
     const hipError_t e = hipMemcpyAsync(plan->dev_buf, plan->host_buf, bytes, hipMemcpyHostToDevice,
                                         (hipStream_t)stream);
@@ -873,31 +920,32 @@ int ew_unpack_snapshot(const ew_plan_t *plan, const void *stage, const void *con
     if (st.nblk[k] > max_blk) max_blk = st.nblk[k];
   }
   std::lock_guard<std::mutex> lock(g_scratch.mu);
-  ew_cksum_t *slots = region_for(stream);
-  if (!slots) return EW_ENOMEM;  // every scratch region is owned by another stream
+  Region *region = nullptr;
+  ew_cksum_t *slots = acquire_region(stream, &region);
+  if (!slots) return EW_ENOMEM;  // only for a capturing stream that owns no region (see acquire_region)
   hipLaunchKernelGGL(ew_zero_records_kernel, dim3((2 * max_blk + kThreads - 1) / kThreads, plan->new_dp),
                      dim3(kThreads), 0, stream, st);
   EW_HIP(hipGetLastError());
-  const uint32_t nruns = (uint32_t)tt.runs.size();
   const uint32_t per_lane = 16;
   for (uint64_t t0 = 0; t0 < tt.ntiles; t0 += kRegionSlots) {
     const uint64_t n = tt.ntiles - t0 < kRegionSlots ? tt.ntiles - t0 : kRegionSlots;
     const uint64_t fold_grid = ((n + per_lane - 1) / per_lane + kThreads - 1) / kThreads;
     if (elem_size == 2) {
-      hipLaunchKernelGGL(ew_unpack_snap_kernel<2>, dim3((uint32_t)n), dim3(kThreads), 0, stream, tt.d_runs, nruns,
-                         tt.d_templ, t0, tabs, st, slots);
+      hipLaunchKernelGGL(ew_unpack_snap_kernel<2>, dim3((uint32_t)n), dim3(kThreads), 0, stream, tt.dev, t0, tabs, st,
+                         slots);
       EW_HIP(hipGetLastError());
-      hipLaunchKernelGGL(ew_fold_tiles_kernel<2>, dim3((uint32_t)fold_grid), dim3(kThreads), 0, stream, tt.d_runs,
-                         nruns, tt.d_templ, t0, n, per_lane, st, slots);
+      hipLaunchKernelGGL(ew_fold_tiles_kernel<2>, dim3((uint32_t)fold_grid), dim3(kThreads), 0, stream, tt.dev, t0, n,
+                         per_lane, st, slots);
     } else {
-      hipLaunchKernelGGL(ew_unpack_snap_kernel<4>, dim3((uint32_t)n), dim3(kThreads), 0, stream, tt.d_runs, nruns,
-                         tt.d_templ, t0, tabs, st, slots);
+      hipLaunchKernelGGL(ew_unpack_snap_kernel<4>, dim3((uint32_t)n), dim3(kThreads), 0, stream, tt.dev, t0, tabs, st,
+                         slots);
       EW_HIP(hipGetLastError());
-      hipLaunchKernelGGL(ew_fold_tiles_kernel<4>, dim3((uint32_t)fold_grid), dim3(kThreads), 0, stream, tt.d_runs,
-                         nruns, tt.d_templ, t0, n, per_lane, st, slots);
+      hipLaunchKernelGGL(ew_fold_tiles_kernel<4>, dim3((uint32_t)fold_grid), dim3(kThreads), 0, stream, tt.dev, t0, n,
+                         per_lane, st, slots);
     }
     EW_HIP(hipGetLastError());
   }
+  release_region(region, stream);
   return EW_OK;
 }
 
@@ -937,10 +985,7 @@ int ew_memcpy(const void *src, void *dst, uint64_t nbytes, void *stream) {
 
 int ew_set_param(const char *name, int64_t value) {
   if (!name) return EW_EINVAL;
-  if (!std::strcmp(name, "copy_wgs_per_cu")) {
-    if (value < 0 || value > 64) return EW_EINVAL;
-    g_copy_wgs_per_cu = value;
-  } else if (!std::strcmp(name, "cksum_sub_bytes")) {
+  if (!std::strcmp(name, "cksum_sub_bytes")) {
     if (value < 4096 || value > (int64_t)EW_CKSUM_BLOCK || (value & (value - 1))) return EW_EINVAL;
     g_cksum_sub_bytes = value;
   } else if (!std::strcmp(name, "cksum_wgs_per_cu")) {
@@ -966,7 +1011,6 @@ int ew_set_param(const char *name, int64_t value) {
 
 int64_t ew_get_param(const char *name) {
   if (!name) return -1;
-  if (!std::strcmp(name, "copy_wgs_per_cu")) return g_copy_wgs_per_cu;
   if (!std::strcmp(name, "cksum_sub_bytes")) return g_cksum_sub_bytes;
   if (!std::strcmp(name, "cksum_wgs_per_cu")) return g_cksum_wgs_per_cu;
   if (!std::strcmp(name, "cksum_mode")) return g_cksum_mode;

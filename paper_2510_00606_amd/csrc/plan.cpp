@@ -352,6 +352,16 @@ void build_tile_table(const ew_plan_t &plan, int which, uint32_t tile_elems, uin
     if (whole > 0) emit(0, period, whole);
     if (rest > 0) emit(whole * period, rest, 1);
   }
+  // coarse index: about four buckets per record
+  out.shift = 0;
+  while ((out.ntiles >> out.shift) > 4 * (uint64_t)out.runs.size() + 64) ++out.shift;
+  out.coarse.assign((size_t)(out.ntiles >> out.shift) + 1, 0);
+  uint32_t r = 0;
+  for (size_t b = 0; b < out.coarse.size(); ++b) {
+    const uint64_t t = (uint64_t)b << out.shift;
+    while (r + 1 < out.runs.size() && out.runs[r + 1].tile_begin <= t) ++r;
+    out.coarse[b] = r;
+  }
 }
 
 }  // namespace ew
@@ -461,8 +471,7 @@ int ew_plan_tiles(const ew_plan_t *p, int which, uint32_t tile_elems, uint32_t a
     if (count == 0) return EW_OK;
     if (first > tt.ntiles || count > tt.ntiles - first) return EW_EINVAL;
     for (uint64_t i = 0; i < count; ++i) {
-      const ew::TileRef r =
-          ew::decode_tile(tt.runs.data(), (uint32_t)tt.runs.size(), tt.templ.data(), first + i);
+      const ew::TileRef r = ew::decode_tile(tt.host_ref(), first + i);
       out[i].src_off = r.src_off;
       out[i].dst_off = r.dst_off;
       out[i].len = r.len;

@@ -72,35 +72,44 @@ struct TileRef {
 #else
 #define EW_HD inline
 #endif
-EW_HD TileRef decode_tile(const RunT *runs, uint32_t nruns, const TileT *templ, uint64_t t) {
-  uint32_t lo = 0, hi = nruns - 1;
-  while (lo < hi) {  // last run whose first tile is <= t
-    const uint32_t mid = (lo + hi + 1) >> 1;
-    if (runs[mid].tile_begin <= t)
-      lo = mid;
-    else
-      hi = mid - 1;
-  }
-  const RunT run = runs[lo];
+// What a kernel needs to decode tile ids: the records, a coarse index over tile ids (entry b = the
+// record holding tile b << shift, so the search below starts at most a few records early whatever
+// the number of records: a plan with 1000 records decodes as fast as one with 14), the templates.
+struct TableRef {
+  const RunT *runs;
+  const uint32_t *coarse;
+  const TileT *templ;
+  uint32_t nruns;
+  uint32_t shift;
+};
+
+EW_HD TileRef decode_tile(const TableRef &tb, uint64_t t) {
+  uint32_t r = tb.coarse[t >> tb.shift];
+  while (r + 1 < tb.nruns && tb.runs[r + 1].tile_begin <= t) ++r;  // last record whose first tile is <= t
+  const RunT run = tb.runs[r];
   const uint64_t local = t - run.tile_begin;
   const uint64_t unit = local / run.tiles_per_unit;
-  const TileT tl = templ[run.templ_begin + (uint32_t)(local - unit * run.tiles_per_unit)];
-  TileRef r;
-  r.src_off = tl.src_off + unit * tl.src_stride;
-  r.dst_off = tl.dst_off + unit * tl.dst_stride;
-  r.len = tl.len;
-  r.src_buf = tl.src_buf;
-  r.dst_buf = tl.dst_buf;
-  return r;
+  const TileT tl = tb.templ[run.templ_begin + (uint32_t)(local - unit * run.tiles_per_unit)];
+  TileRef ref;
+  ref.src_off = tl.src_off + unit * tl.src_stride;
+  ref.dst_off = tl.dst_off + unit * tl.dst_stride;
+  ref.len = tl.len;
+  ref.src_buf = tl.src_buf;
+  ref.dst_buf = tl.dst_buf;
+  return ref;
 }
 
 struct TileTable {       // host-side description of one (which, elem size) table
   std::vector<RunT> runs;
   std::vector<TileT> templ;
+  std::vector<uint32_t> coarse;
+  uint32_t shift = 0;
   uint64_t ntiles = 0;
-  // device addresses inside the plan's single device buffer
-  const RunT *d_runs = nullptr;
-  const TileT *d_templ = nullptr;
+  TableRef host_ref() const {
+    return TableRef{runs.data(), coarse.data(), templ.data(), (uint32_t)runs.size(), shift};
+  }
+  // the same table inside the plan's single device buffer
+  TableRef dev = {nullptr, nullptr, nullptr, 0, 0};
 };
 
 }  // namespace ew

@@ -16,7 +16,7 @@ MIB = 1 << 20
 
 @pytest.fixture(autouse=True)
 def default_params():
-    saved = {k: ew.ew_get_param(k) for k in ("tile_bytes", "tile_elems", "tile_align_bytes", "copy_wgs_per_cu", "cksum_sub_bytes", "cksum_wgs_per_cu",
+    saved = {k: ew.ew_get_param(k) for k in ("tile_bytes", "tile_elems", "tile_align_bytes", "cksum_sub_bytes", "cksum_wgs_per_cu",
                                               "cksum_mode")}
     yield
     for k, v in saved.items():
@@ -226,9 +226,10 @@ def test_reshard_medium(case, elem_size):
     reshard_case(*case, elem_size, rng)
 
 
-@pytest.mark.parametrize("tile_elems,wgs", [(0, 0), (0, 2), (64, 0), (1000, 1), (4096, 8), (8192, 0), (65536, 4), (1 << 20, 2)])
-def test_reshard_launch_shapes(tile_elems, wgs):
-    ew.ew_set_param("copy_wgs_per_cu", wgs)
+@pytest.mark.parametrize("tile_elems,align", [(0, 128), (0, 0), (0, 64), (64, 128), (1000, 16), (4096, 256), (8192, 0), (65536, 128),
+                                              (1 << 20, 128)])
+def test_reshard_launch_shapes(tile_elems, align):
+    ew.ew_set_param("tile_align_bytes", align)
     rng = np.random.default_rng(tile_elems)
     for es in (2, 4):
         reshard_case(8, 7, 0xFF & ~(1 << 5), 3_000_000 + 8 * 37, 262144, es, rng, tile_elems)
@@ -266,8 +267,8 @@ def test_plain_copy_yardstick():
 
 
 def test_snapshot_on_many_streams():
-    """The first streams get a scratch region each, later ones take the scratch-free kernel;
-    every result is the oracle's."""
+    """More streams than scratch regions: regions change hands (the new owner waits on the device
+    for the previous use); every result is the oracle's."""
     rng = np.random.default_rng(77)
     streams = [torch.cuda.Stream() for _ in range(6)]
     nbytes = 5 * MIB + 4096 + 9
@@ -314,3 +315,39 @@ def test_snapshot_longer_than_one_scratch_pass():
     total = int(v.sum().item()) & ((1 << 64) - 1)
     tail = int.from_bytes(bytes([0xA7] * (nbytes % 8)), "little")
     assert (int(got[:, 0].sum(dtype=np.uint64)) & ((1 << 64) - 1)) == (total + tail) & ((1 << 64) - 1)
+
+
+def test_fused_unpack_on_many_streams():
+    """Six streams take turns with four scratch regions; each stream's result is the oracle's."""
+    rng = np.random.default_rng(123)
+    Do, Dn, mask, N, C, es = 5, 4, 0b11011, 1_200_000, 40_000, 4
+    starts = layout.unit_starts(N, C)
+    alive = layout.alive_list(Do, mask)
+    lens = layout.shard_lengths(starts, Do)
+    plan = ew.ew_plan(Do, Dn, mask, N, C)
+    ew.ew_plan_upload(plan, 0, stream())
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream() for _ in range(6)]
+    jobs = []
+    for s in streams:
+        data = random_shards(lens, es, rng)
+        want = layout.reshard([d if alive[j] else None for j, d in enumerate(data)],
+                              [None if alive[j] else d for j, d in enumerate(data)], Do, Dn, mask, starts)
+        old = [to_dev(d, es) if alive[j] else None for j, d in enumerate(data)]
+        snaps = [None if alive[j] else to_dev(d, es) for j, d in enumerate(data)]
+        stage = torch.zeros(plan.stage_len, dtype=torch.int32, device=DEV)
+        new = [torch.zeros(plan.new_shard_len(k), dtype=torch.int32, device=DEV) for k in range(Dn)]
+        nsn = [torch.zeros_like(t) for t in new]
+        ck = [torch.zeros((ew.num_blocks(t.numel() * es), 2), dtype=torch.int64, device=DEV) for t in new]
+        jobs.append((s, old, snaps, stage, new, nsn, ck, want))
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for (s, old, snaps, stage, new, nsn, ck, want) in jobs:
+            ew.ew_pack(plan, old, snaps, stage, es, s.cuda_stream)
+            ew.ew_unpack_snapshot(plan, stage, old, snaps, new, nsn, ck, es, s.cuda_stream)
+    torch.cuda.synchronize()
+    for (s, old, snaps, stage, new, nsn, ck, want) in jobs:
+        for k in range(Dn):
+            assert np.array_equal(np_bits(new[k]), want[k]) and np.array_equal(np_bits(nsn[k]), want[k])
+            assert np.array_equal(ck[k].cpu().numpy().view(np.uint64), checksum.block_checksums(want[k]))
+    plan.close()
