@@ -345,8 +345,10 @@ void build_tile_table(const ew_plan_t &plan, int which, uint32_t tile_elems, uin
           }
         }
       rt.tiles_per_unit = (uint32_t)(out.templ.size() - rt.templ_begin);
-      out.runs.push_back(rt);
       out.ntiles += (uint64_t)rt.tiles_per_unit * reps;
+      rt.tile_end = out.ntiles;
+      rt.pad = 0;
+      out.runs.push_back(rt);
     };
     const uint64_t whole = run.n_units / period, rest = run.n_units % period;
     if (whole > 0) emit(0, period, whole);

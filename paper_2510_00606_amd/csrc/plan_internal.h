@@ -47,10 +47,12 @@ static_assert(sizeof(TileT) == 48, "tile template must stay 48 bytes");
 // run, unit after unit.  Records are ordered destination-major (see build_tile_table).
 struct RunT {
   uint64_t tile_begin;      // global id of the record's first tile
-  uint32_t tiles_per_unit;  // templates per unit (> 0)
+  uint64_t tile_end;        // one past its last tile (= the next record's tile_begin)
+  uint32_t tiles_per_unit;  // templates per repetition (> 0)
   uint32_t templ_begin;     // index of the record's first template
+  uint64_t pad;
 };
-static_assert(sizeof(RunT) == 16, "run record must stay 16 bytes");
+static_assert(sizeof(RunT) == 32, "run record must stay 32 bytes (one aligned scalar load)");
 
 constexpr uint32_t kSrcLive = 0;
 constexpr uint32_t kSrcSnap = EW_MAX_DP;
@@ -85,8 +87,9 @@ struct TableRef {
 
 EW_HD TileRef decode_tile(const TableRef &tb, uint64_t t) {
   uint32_t r = tb.coarse[t >> tb.shift];
-  while (r + 1 < tb.nruns && tb.runs[r + 1].tile_begin <= t) ++r;  // last record whose first tile is <= t
-  const RunT run = tb.runs[r];
+  RunT run = tb.runs[r];
+  while (t >= run.tile_end) run = tb.runs[++r];  // usually no step: the index lands on the record
+
   const uint64_t local = t - run.tile_begin;
   const uint64_t unit = local / run.tiles_per_unit;
   const TileT tl = tb.templ[run.templ_begin + (uint32_t)(local - unit * run.tiles_per_unit)];
