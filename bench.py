@@ -9,6 +9,8 @@ One step = one pass over one DP group's state (all four arrays P/W/M/V resident 
   a6+a7        ew_unpack_snapshot: arena + local segments -> new shards, their snapshot copies and
                the checksums of the new shards, every element read once
                (--unfused: ew_unpack, then ew_snapshot of every new rank's partition)
+The 70B stage does not fit 288 GB with all four arrays resident (299 GB): there the step is measured
+one state array at a time (that array resident before its own timed steps) and the four are summed.
 `value` is the algorithmic bytes (read + written) of the kernels as run divided by the step's wall
 time; `ms_per_step` is the figure that shows what fusing a6 and a7 saves.  The path not chosen for
 the headline is timed too, after the timed region, and reported under "other_path".
@@ -41,7 +43,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="7b_stage", choices=["tiny", "7b_stage", "13b_stage"])
+    ap.add_argument("--workload", default="7b_stage", choices=["tiny", "7b_stage", "13b_stage", "70b_stage"],
+                    help="70b_stage does not fit 288 GB with all four arrays resident: it is measured one "
+                         "array at a time (each array resident before its own timed steps) and summed")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-units", type=int, default=8192)
     ap.add_argument("--unfused", action="store_true",
@@ -69,28 +73,53 @@ def read_traffic(kernel_key):
     return None
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (all simulated DP ranks live in one MI355X's HBM); "
-              f"--gpus {args.gpus} is not supported", file=sys.stderr)
-        sys.exit(2)
+def merge_paths(parts):
+    """Sums the per-array measurements of one path."""
+    out = {"ms_per_step": 0.0, "plan_ms": 0.0, "phase_ms": {}, "bytes_phase": {}, "launches": {}}
+    for p in parts:
+        out["ms_per_step"] += p["ms_per_step"]
+        out["plan_ms"] += p["plan_ms"]
+        for key in ("phase_ms", "bytes_phase", "launches"):
+            for ph, v in p[key].items():
+                out[key][ph] = out[key].get(ph, 0) + v
+    return out
 
-    import numpy as np
-    import torch
 
-    import paper_2510_00606_amd as ew
-    from paper_2510_00606_amd import configs, synth
+def summarise(path, workload_name):
+    """value, per-phase table and the roofline of the dominant kernel of one (merged) path."""
+    phase_ms, bytes_phase, launches = path["phase_ms"], path["bytes_phase"], path["launches"]
+    kernels = {}
+    for ph in phase_ms:
+        if phase_ms[ph] > 0:
+            gbs = bytes_phase[ph] / phase_ms[ph] / 1e6
+            kernels[ph] = {"ms": round(phase_ms[ph], 4), "launches": launches[ph], "GB": round(bytes_phase[ph] / 1e9, 4),
+                           "GB/s": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4)}
+    # dominant kernel: the one whose launches take the most time in a step
+    groups = {}
+    for ph in phase_ms:
+        g = groups.setdefault(KERNEL_OF[ph], [0.0, 0.0, 0])
+        g[0] += phase_ms[ph]
+        g[1] += bytes_phase[ph]
+        g[2] += launches[ph]
+    dom = max(groups, key=lambda k: groups[k][0])
+    d_ms, d_bytes, d_launches = groups[dom]
+    achieved = d_bytes / d_ms / 1e6
+    roofline = {"kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(f"{dom.split()[-1]}/{workload_name}"),
+                "bytes_per_launch": round(d_bytes / d_launches), "avg_launch_us": round(d_ms / d_launches * 1e3, 2)}
+    step_bytes = sum(bytes_phase.values())
+    return {"ms_per_step": path["ms_per_step"], "value": step_bytes / path["ms_per_step"] / 1e6,
+            "step_GB": step_bytes / 1e9, "plan_ms": path["plan_ms"], "kernels": kernels, "roofline": roofline}
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible; there is no CPU fallback", file=sys.stderr)
-        sys.exit(2)
+
+def measure(args, ew, synth, torch, w, starts, A, keep_state):
+    """Everything that needs the state arrays `A` of workload `w` resident in HBM: the timed steps of
+    the headline path, the other path, the plain-copy yardstick and the stand-alone reshard time."""
     dev = "cuda:0"
-    torch.cuda.set_device(0)
     st = torch.cuda.current_stream().cuda_stream
-    w = configs.ALL[args.workload]()
-    starts = w.unit_starts()
-
+    bpe = sum(synth.ELEM_SIZE[a] for a in A)
+    es = synth.ELEM_SIZE
+    numel = w.numel
     # ---------------- setup (untimed): state resident in HBM
     plan0 = ew.ew_plan_bounds(w.old_dp, w.new_dp, w.alive_mask, starts)
     alive = [(w.alive_mask >> j) & 1 for j in range(w.old_dp)]
@@ -98,7 +127,6 @@ def main():
     new_len = [plan0.new_shard_len(k) for k in range(w.new_dp)]
     stage_len = plan0.stage_len
     plan0.close()
-    A = synth.ARRAYS
     es = synth.ELEM_SIZE
     old = {a: [synth.fill(w.seed, j, a, 0, old_len[j], dev) for j in range(w.old_dp)] for a in A}
     snap = {a: [torch.empty_like(t) for t in old[a]] for a in A}
@@ -122,17 +150,17 @@ def main():
     ck_new = 16 * sum(int(t.shape[0]) for a in A for t in nsums[a])
 
     def phase_table(unfused):
-        b = {"snapshot_old": sum(2 * n * 14 for n in old_len) + ck_old,
-             "verify": sum(old_len[j] * 14 for j in w.failed),
-             "pack": 2 * 14 * n_remote}
-        n = {"snapshot_old": 4 * w.old_dp, "verify": 4 * len(w.failed), "pack": 4}
+        b = {"snapshot_old": sum(2 * n * bpe for n in old_len) + ck_old,
+             "verify": sum(old_len[j] * bpe for j in w.failed),
+             "pack": 2 * bpe * n_remote}
+        n = {"snapshot_old": len(A) * w.old_dp, "verify": len(A) * len(w.failed), "pack": len(A)}
         if unfused:
-            b["unpack"] = 2 * 14 * numel
-            b["snapshot_new"] = sum(2 * x * 14 for x in new_len) + ck_new
-            n.update({"unpack": 4, "snapshot_new": 4 * w.new_dp})
+            b["unpack"] = 2 * bpe * numel
+            b["snapshot_new"] = sum(2 * x * bpe for x in new_len) + ck_new
+            n.update({"unpack": len(A), "snapshot_new": len(A) * w.new_dp})
         else:
-            b["unpack_snapshot"] = 3 * 14 * numel + ck_new    # read once, written twice
-            n["unpack_snapshot"] = 4
+            b["unpack_snapshot"] = 3 * bpe * numel + ck_new    # read once, written twice
+            n["unpack_snapshot"] = len(A)
         return b, n
 
     def step(unfused, record):
@@ -194,32 +222,8 @@ def main():
             p.close()
         assert int(n_bad.item()) == 0, "verification of an intact snapshot reported bad blocks"
         phase_ms = {ph: sum(ev[i].elapsed_time(ev[i + 1]) for _, ev in records) / steps for i, ph in enumerate(phases)}
-        kernels = {}
-        for ph in phases:
-            if phase_ms[ph] > 0:
-                gbs = bytes_phase[ph] / phase_ms[ph] / 1e6
-                kernels[ph] = {"ms": round(phase_ms[ph], 4), "launches": launches[ph],
-                               "GB": round(bytes_phase[ph] / 1e9, 4), "GB/s": round(gbs, 1),
-                               "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4)}
-        # dominant kernel: the one whose launches take the most time in a step
-        groups = {}
-        for ph in phases:
-            g = groups.setdefault(KERNEL_OF[ph], [0.0, 0.0, 0])
-            g[0] += phase_ms[ph]
-            g[1] += bytes_phase[ph]
-            g[2] += launches[ph]
-        dom = max(groups, key=lambda k: groups[k][0])
-        d_ms, d_bytes, d_launches = groups[dom]
-        achieved = d_bytes / d_ms / 1e6
-        roofline = {"kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                    "traffic": read_traffic(f"{dom.split()[-1]}/{w.name}"),
-                    "bytes_per_launch": round(d_bytes / d_launches),
-                    "avg_launch_us": round(d_ms / d_launches * 1e3, 2)}
-        step_bytes = sum(bytes_phase.values())
-        return {"ms_per_step": elapsed / steps * 1e3, "value": step_bytes / (elapsed / steps) / 1e9,
-                "step_GB": step_bytes / 1e9, "plan_ms": sum(r[0] for r in records) / steps * 1e3,
-                "kernels": kernels, "roofline": roofline}
+        return {"ms_per_step": elapsed / steps * 1e3, "plan_ms": sum(r[0] for r in records) / steps * 1e3,
+                "phase_ms": phase_ms, "bytes_phase": bytes_phase, "launches": launches}
 
     # ---------------- the timed region (inside run_path): exactly K steps of the headline path
     head = run_path(args.unfused, args.steps, args.warmup)
@@ -229,8 +233,8 @@ def main():
     # i.e. what a copy with nothing else to do reaches on this GPU; these launches are also the
     # known-size dispatches (ybytes read, ybytes written) that the profiler's byte counters are
     # calibrated with
-    ysrc, ydst = old["W"][0], snap["W"][0]
-    ybytes = (old_len[0] * 4) & ~15
+    ysrc, ydst = old[A[-1]][0], snap[A[-1]][0]
+    ybytes = (old_len[0] * es[A[-1]]) & ~15
     for _ in range(3):
         ew.ew_memcpy(ysrc, ydst, ybytes, st)
     y0, y1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -258,26 +262,7 @@ def main():
         rp.close()
     reshard_only_ms = sorted(reshard_runs)[len(reshard_runs) // 2]
 
-    names = {True: "unfused (ew_unpack, then ew_snapshot of the new shards)",
-             False: "fused (ew_unpack_snapshot also writes the new shards' snapshots and checksums)"}
-    out = {
-        "metric": "reshard+snapshot GB/s on one MI355X and % of HBM peak; time to reshard one stage",
-        "value": round(head["value"], 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(head["ms_per_step"], 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "u64", "data": "synthetic",
-        "config": {"workload": w.name, "note": w.note, "numel": numel, "state_bytes": 14 * numel, "old_dp": w.old_dp,
-                   "new_dp": w.new_dp, "failed": w.failed, "units": int(len(starts) - 1),
-                   "remote_fraction": round(n_remote / numel, 4), "arrays": "bf16 P + fp32 W, M, V"},
-        "frac_of_hbm_peak": round(head["value"] / HBM_PEAK_GBS, 4),
-        "path": names[args.unfused],
-        "reshard_one_stage_ms": round(reshard_only_ms, 3),
-        "reshard_useful_GBps": round(14 * numel / reshard_only_ms / 1e6, 1),
-        "plan_ms": round(head["plan_ms"], 3),
-        "step_GB": round(head["step_GB"], 3),
-        "kernels": head["kernels"],
-        "plain_copy_GBps": round(copy_gbs, 1),
-        "roofline": head["roofline"],
-    }
+    tiny_latency = None
     if w.name == "tiny":
         # cache-resident and launch bound: read these as latencies, not as fractions of HBM peak.  The
         # device part of a step (a2..a7, ~45 launches) replayed from a HIP graph vs issued call by call.
@@ -312,15 +297,83 @@ def main():
                 fn()
             torch.cuda.synchronize()
             lat[name + "_us"] = round((time.perf_counter() - t0) / 50 * 1e6, 1)
-        out["tiny_step_latency"] = lat
+        tiny_latency = lat
         gplan.close()
+    return {"head": head, "other": other, "copy_gbs": copy_gbs, "reshard_only_ms": reshard_only_ms, "n_remote": n_remote,
+            "old_len": old_len, "keep": (old, alive) if keep_state else None, "tiny_latency": tiny_latency}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (all simulated DP ranks live in one MI355X's HBM); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2510_00606_amd as ew
+    from paper_2510_00606_amd import configs, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; there is no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    st = torch.cuda.current_stream().cuda_stream
+    w = configs.ALL[args.workload]()
+    starts = w.unit_starts()
+
+    A = list(synth.ARRAYS)
+    es = synth.ELEM_SIZE
+    numel = w.numel
+    # all four arrays resident at once, except where that exceeds the GPU's memory
+    residency = [[a] for a in A] if w.name == "70b_stage" else [A]
+    parts = []
+    for group in residency:
+        parts.append(measure(args, ew, synth, torch, w, starts, group, keep_state=(len(residency) == 1)))
+        torch.cuda.empty_cache()
+    head = summarise(merge_paths([p["head"] for p in parts]), w.name)
+    other = None if parts[0]["other"] is None else summarise(merge_paths([p["other"] for p in parts]), w.name)
+    copy_gbs = parts[-1]["copy_gbs"]
+    reshard_only_ms = sum(p["reshard_only_ms"] for p in parts)
+    n_remote = parts[0]["n_remote"]
+    old_len = parts[0]["old_len"]
+    old, alive = parts[0]["keep"] if parts[0]["keep"] else (None, None)
+    st = torch.cuda.current_stream().cuda_stream
+
+    names = {True: "unfused (ew_unpack, then ew_snapshot of the new shards)",
+             False: "fused (ew_unpack_snapshot also writes the new shards' snapshots and checksums)"}
+    out = {
+        "metric": "reshard+snapshot GB/s on one MI355X and % of HBM peak; time to reshard one stage",
+        "value": round(head["value"], 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(head["ms_per_step"], 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u64", "data": "synthetic",
+        "config": {"workload": w.name, "note": w.note, "numel": numel, "state_bytes": 14 * numel, "old_dp": w.old_dp,
+                   "new_dp": w.new_dp, "failed": w.failed, "units": int(len(starts) - 1),
+                   "remote_fraction": round(n_remote / numel, 4), "arrays": "bf16 P + fp32 W, M, V"},
+        "frac_of_hbm_peak": round(head["value"] / HBM_PEAK_GBS, 4),
+        "path": names[args.unfused],
+        "reshard_one_stage_ms": round(reshard_only_ms, 3),
+        "reshard_useful_GBps": round(14 * numel / reshard_only_ms / 1e6, 1),
+        "plan_ms": round(head["plan_ms"], 3),
+        "step_GB": round(head["step_GB"], 3),
+        "kernels": head["kernels"],
+        "plain_copy_GBps": round(copy_gbs, 1),
+        "roofline": head["roofline"],
+    }
+    if parts[0]["tiny_latency"] is not None:
+        out["tiny_step_latency"] = parts[0]["tiny_latency"]
     if other is not None:
         out["other_path"] = {"path": names[not args.unfused], "ms_per_step": round(other["ms_per_step"], 3),
                              "value": round(other["value"], 1), "step_GB": round(other["step_GB"], 3),
                              "kernels": other["kernels"]}
 
     # ---------------- CPU baseline: the oracle as it stands, one core, on a bounded sample
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and old is None:
+        out["cpu_baseline"] = None   # measured at the workloads whose state is resident all at once (default: 7b_stage)
+    if not args.no_cpu_baseline and old is not None:
         from oracle import checksum as o_ck
         from oracle import layout as o_lay
         n_units = min(args.cpu_sample_units, len(starts) - 1)
@@ -361,7 +414,7 @@ def main():
 
     # ---------------- layer migration, contiguous vs interleaved assignment (Sec. 6.3); not part of `value`
     if not args.no_migration and w.name != "tiny":
-        del old, snap, sums, stage, new, nsnap, nsums, got, old_after, snap_used
+        del old, parts
         torch.cuda.empty_cache()
         out["layer_migration"] = migration_compare(ew, configs, synth, torch, st, dev)
     if not args.no_grad_snapshot and w.name != "tiny":
