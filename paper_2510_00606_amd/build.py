@@ -12,8 +12,15 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libelaswave.so")
-SOURCES = [os.path.join(HERE, "csrc", "plan.cpp"), os.path.join(HERE, "csrc", "partition.cpp"),
-           os.path.join(HERE, "csrc", "kernels.hip"), os.path.join(HERE, "csrc", "adam.hip")]
+SOURCES = [os.path.join(HERE, "csrc", name) for name in (
+    "plan.cpp",              # planner: overlap in run-length form, tile tables, queries
+    "partition.cpp",         # minimax layer partition
+    "runtime.hip",           # error capture, knobs, scratch regions, ew_set_param & co.
+    "copy.hip",              # ew_plan_upload, ew_pack, ew_unpack, ew_memcpy
+    "cksum.hip",             # ew_snapshot, ew_verify
+    "unpack_snapshot.hip",   # ew_unpack_snapshot
+    "adam.hip",              # ew_adam_step, ew_grad_ship, host replay
+)]
 
 
 def hipcc_path() -> str:

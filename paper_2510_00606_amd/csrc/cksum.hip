@@ -1,0 +1,295 @@
+// Per-step snapshot copy fused with the per-block checksum (Sec. 5.1 and the online verification
+// named in the abstract), its read-only form, and the ordered list of blocks whose checksum
+// changed.  A block is EW_CKSUM_BLOCK = 1 MiB; its record is the wrapping sum and the xor of its
+// little-endian 64-bit words, the last word zero-padded.  Both operations commute, so the bits do
+// not depend on the order in which partial results meet.  HBM-bandwidth bound, no MFMA.
+#include "device_util.h"
+#include "runtime.h"
+
+namespace {
+
+using ew::block_fold;
+using ew::fold;
+using ew::kThreads;
+using ew::kUnroll;
+using ew::load16;
+using ew::store16;
+using ew::u32x4;
+
+// Streaming form.  A block is cut into sub-blocks of `sub` bytes (a power of two, 4 KiB..1 MiB); a
+// workgroup streams one sub-block, folding its words into (sum, xor) per lane, then across the
+// workgroup.  With sub < 1 MiB the partial results of a block meet in its record through 64-bit
+// atomics (the records are zeroed first).  Serves any alignment; it is the fast form for read-only
+// passes and the fallback for copies.
+template <bool COPY, bool ALIGNED>
+__global__ __launch_bounds__(kThreads) void ew_cksum_kernel(const char *__restrict__ src, char *__restrict__ dst,
+                                                            uint64_t nbytes, ew_cksum_t *out, uint32_t sub,
+                                                            uint32_t accumulate) {
+  __shared__ uint64_t lds_sum[kThreads / 64];
+  __shared__ uint64_t lds_xor[kThreads / 64];
+  const uint64_t nsub = (nbytes + sub - 1) / sub;
+  for (uint64_t c = blockIdx.x; c < nsub; c += gridDim.x) {
+    const uint64_t begin = c * sub;
+    const uint64_t left = nbytes - begin;
+    const uint32_t n = left < sub ? (uint32_t)left : sub;
+    uint64_t sum = 0, xr = 0;
+    if (ALIGNED) {
+      const u32x4 *sv = reinterpret_cast<const u32x4 *>(src + begin);
+      u32x4 *dv = reinterpret_cast<u32x4 *>(dst + begin);
+      const uint32_t nvec = n >> 4;
+      uint32_t i = threadIdx.x;
+      for (; i + (kUnroll - 1) * kThreads < nvec; i += kUnroll * kThreads) {
+        u32x4 r[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) r[u] = load16(sv + i + u * kThreads);
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+          if (COPY) store16(dv + i + u * kThreads, r[u]);
+          fold(r[u], sum, xr);
+        }
+      }
+      for (; i < nvec; i += kThreads) {
+        const u32x4 r = load16(sv + i);
+        if (COPY) store16(dv + i, r);
+        fold(r, sum, xr);
+      }
+      // fewer than 16 trailing bytes (only at the very end of the buffer): one lane copies
+      // them and folds them as up to two zero-padded little-endian words
+      const uint32_t done = nvec << 4;
+      if (threadIdx.x == 0 && done < n) {
+        uint64_t w[2] = {0, 0};
+        for (uint32_t b = done; b < n; ++b) {
+          const uint8_t v = (uint8_t)src[begin + b];
+          if (COPY) dst[begin + b] = (char)v;
+          w[(b - done) >> 3] |= (uint64_t)v << (8 * ((b - done) & 7));
+        }
+        sum += w[0] + w[1];
+        xr ^= w[0] ^ w[1];
+      }
+    } else {
+      // unaligned base: byte loads, one 64-bit word per lane per step
+      const uint32_t nwords = (n + 7) >> 3;
+      for (uint32_t wi = threadIdx.x; wi < nwords; wi += kThreads) {
+        uint64_t w = 0;
+        const uint32_t b0 = wi << 3;
+        const uint32_t nb = (n - b0) < 8 ? (n - b0) : 8;
+        for (uint32_t b = 0; b < nb; ++b) {
+          const uint8_t v = (uint8_t)src[begin + b0 + b];
+          if (COPY) dst[begin + b0 + b] = (char)v;
+          w |= (uint64_t)v << (8 * b);
+        }
+        sum += w;
+        xr ^= w;
+      }
+    }
+    block_fold(sum, xr, lds_sum, lds_xor);
+    if (threadIdx.x == 0) {
+      ew_cksum_t *rec = out + (begin >> 20);
+      if (accumulate) {
+        atomicAdd(reinterpret_cast<unsigned long long *>(&rec->sum), (unsigned long long)sum);
+        atomicXor(reinterpret_cast<unsigned long long *>(&rec->xr), (unsigned long long)xr);
+      } else {
+        rec->sum = sum;
+        rec->xr = xr;
+      }
+    }
+    __syncthreads();  // LDS is reused by the next sub-block of a persistent workgroup
+  }
+}
+
+// Fast form of the copy for 16-byte aligned buffers.  Measured on MI355X, a copy runs fastest as a
+// flood of small workgroups in which every lane moves ONE 128-bit vector (4 KiB per 256-lane
+// workgroup), and 64-bit atomics from many workgroups onto one checksum record serialise badly.
+// So: each workgroup folds its 4 KiB into one (sum, xor) pair and writes it to its own 16-byte
+// slot of a scratch region (no atomics, no zero-fill), and ew_fold_kernel then folds the 256
+// slots of every 1 MiB block into the block's record.
+template <bool COPY>
+__global__ __launch_bounds__(kThreads) void ew_cksum_slots_kernel(const u32x4 *__restrict__ src,
+                                                                  u32x4 *__restrict__ dst, uint64_t nbytes,
+                                                                  ew_cksum_t *__restrict__ slots) {
+  static_assert(kThreads == 256, "one slot per 4 KiB assumes 256 lanes x 16 bytes");
+  __shared__ uint64_t lds_sum[kThreads / 64];
+  __shared__ uint64_t lds_xor[kThreads / 64];
+  const uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+  const uint64_t nvec = nbytes >> 4;
+  uint64_t sum = 0, xr = 0;
+  if (i < nvec) {
+    const u32x4 v = load16(src + i);
+    if (COPY) store16(dst + i, v);
+    fold(v, sum, xr);
+  } else if (i == nvec && (nbytes & 15u)) {
+    // fewer than 16 trailing bytes: copied and folded as up to two zero-padded words
+    const char *sb = reinterpret_cast<const char *>(src + nvec);
+    char *db = reinterpret_cast<char *>(dst + nvec);
+    uint64_t w[2] = {0, 0};
+    for (uint32_t b = 0; b < (uint32_t)(nbytes & 15u); ++b) {
+      const uint8_t v = (uint8_t)sb[b];
+      if (COPY) db[b] = (char)v;
+      w[b >> 3] |= (uint64_t)v << (8 * (b & 7));
+    }
+    sum = w[0] + w[1];
+    xr = w[0] ^ w[1];
+  }
+  block_fold(sum, xr, lds_sum, lds_xor);
+  if (threadIdx.x == 0) {
+    ew_cksum_t r;
+    r.sum = sum;
+    r.xr = xr;
+    slots[blockIdx.x] = r;
+  }
+}
+
+// One workgroup per checksum block: folds the block's slots (256 for a full block) into out[b].
+__global__ __launch_bounds__(kThreads) void ew_fold_kernel(const ew_cksum_t *__restrict__ slots, uint64_t nslots,
+                                                           ew_cksum_t *__restrict__ out) {
+  __shared__ uint64_t lds_sum[kThreads / 64];
+  __shared__ uint64_t lds_xor[kThreads / 64];
+  constexpr uint32_t kSlotsPerBlock = EW_CKSUM_BLOCK / 4096;
+  uint64_t sum = 0, xr = 0;
+  for (uint32_t t = threadIdx.x; t < kSlotsPerBlock; t += kThreads) {
+    const uint64_t sidx = (uint64_t)blockIdx.x * kSlotsPerBlock + t;
+    if (sidx < nslots) {
+      const ew_cksum_t r = slots[sidx];
+      sum += r.sum;
+      xr ^= r.xr;
+    }
+  }
+  block_fold(sum, xr, lds_sum, lds_xor);
+  if (threadIdx.x == 0) {
+    ew_cksum_t r;
+    r.sum = sum;
+    r.xr = xr;
+    out[blockIdx.x] = r;
+  }
+}
+
+// Single workgroup: ascending list of differing blocks (stable compaction with ballots), with the
+// (sum difference, xor difference) of each; *n_bad counts all of them, also those beyond cap.
+constexpr int kCmpThreads = 1024;
+__global__ __launch_bounds__(kCmpThreads) void ew_compare_kernel(const ew_cksum_t *__restrict__ got,
+                                                                 const ew_cksum_t *__restrict__ expect,
+                                                                 uint64_t nblocks, uint64_t *n_bad,
+                                                                 uint64_t *bad_blocks, ew_cksum_t *diffs,
+                                                                 uint64_t cap) {
+  __shared__ uint32_t wave_cnt[kCmpThreads / 64];
+  __shared__ uint64_t base;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (threadIdx.x == 0) base = 0;
+  __syncthreads();
+  for (uint64_t b0 = 0; b0 < nblocks; b0 += kCmpThreads) {
+    const uint64_t b = b0 + threadIdx.x;
+    ew_cksum_t g = {0, 0}, e = {0, 0};
+    bool bad = false;
+    if (b < nblocks) {
+      g = got[b];
+      e = expect[b];
+      bad = (g.sum != e.sum) || (g.xr != e.xr);
+    }
+    const uint64_t ballot = __ballot(bad);
+    if (lane == 0) wave_cnt[wave] = (uint32_t)__popcll(ballot);
+    __syncthreads();
+    uint64_t before = base, total = 0;
+    for (int w = 0; w < kCmpThreads / 64; ++w) {
+      if (w < wave) before += wave_cnt[w];
+      total += wave_cnt[w];
+    }
+    if (bad) {
+      const uint64_t slot = before + (uint64_t)__popcll(ballot & ((1ull << lane) - 1ull));
+      if (slot < cap) {
+        bad_blocks[slot] = b;
+        diffs[slot].sum = g.sum - e.sum;
+        diffs[slot].xr = g.xr ^ e.xr;
+      }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) base += total;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *n_bad = base;
+}
+
+template <bool COPY>
+int launch_cksum_streaming(const void *src, void *dst, uint64_t nbytes, ew_cksum_t *out, hipStream_t stream) {
+  const ew::Knobs &k = ew::knobs();
+  const uint32_t sub = (uint32_t)k.cksum_sub_bytes;
+  const uint64_t nblocks = (nbytes + EW_CKSUM_BLOCK - 1) / EW_CKSUM_BLOCK;
+  const uint32_t accumulate = sub < EW_CKSUM_BLOCK ? 1u : 0u;
+  if (accumulate) {
+    const int rc = ew::launch_zero(out, nblocks * sizeof(ew_cksum_t), stream);
+    if (rc != EW_OK) return rc;
+  }
+  uint64_t grid = (nbytes + sub - 1) / sub;
+  if (k.cksum_wgs_per_cu > 0) {
+    const uint64_t cap = (uint64_t)ew::num_cus() * (uint64_t)k.cksum_wgs_per_cu;
+    if (grid > cap) grid = cap;
+  }
+  if (grid > 0x7fffffffull) grid = 0x7fffffffull;  // the kernel strides over what is left
+  const bool aligned = ((((uintptr_t)src) | (COPY ? (uintptr_t)dst : 0)) & 15u) == 0;
+  if (aligned)
+    hipLaunchKernelGGL((ew_cksum_kernel<COPY, true>), dim3((uint32_t)grid), dim3(kThreads), 0, stream,
+                       (const char *)src, (char *)dst, nbytes, out, sub, accumulate);
+  else
+    hipLaunchKernelGGL((ew_cksum_kernel<COPY, false>), dim3((uint32_t)grid), dim3(kThreads), 0, stream,
+                       (const char *)src, (char *)dst, nbytes, out, sub, accumulate);
+  EW_HIP(hipGetLastError());
+  return EW_OK;
+}
+
+template <bool COPY>
+int launch_cksum(const void *src, void *dst, uint64_t nbytes, ew_cksum_t *out, hipStream_t stream) {
+  const bool aligned = ((((uintptr_t)src) | (COPY ? (uintptr_t)dst : 0)) & 15u) == 0;
+  // Read-only passes (verify) keep the streaming kernel: without stores to overlap, the wave-level
+  // fold of a 4 KiB workgroup costs more than it saves (3.4 vs 6.2 TB/s measured).
+  const int64_t mode = ew::knobs().cksum_mode >= 0 ? ew::knobs().cksum_mode : (COPY ? 0 : 1);
+  if (!aligned || mode != 0) return launch_cksum_streaming<COPY>(src, dst, nbytes, out, stream);
+  // the (slot kernel, fold kernel) pairs of one call must reach the stream back to back
+  std::lock_guard<std::mutex> lock(ew::scratch_mutex());
+  ew::Region *region = nullptr;
+  ew_cksum_t *slots = ew::acquire_region(stream, &region);
+  if (!slots) return launch_cksum_streaming<COPY>(src, dst, nbytes, out, stream);  // needs no scratch
+  constexpr uint64_t kPassBytes = ew::kRegionSlots * 4096;
+  for (uint64_t off = 0; off < nbytes; off += kPassBytes) {
+    const uint64_t n = nbytes - off < kPassBytes ? nbytes - off : kPassBytes;
+    // one workgroup (and slot) per 4 KiB; a partial trailing vector belongs to lane n/16, which
+    // the last workgroup always contains because ceil(n/4096)*256 > n/16 whenever 16 does not divide n
+    const uint64_t grid = (n + 4095) / 4096;
+    const uint64_t nblk = (n + EW_CKSUM_BLOCK - 1) / EW_CKSUM_BLOCK;
+    hipLaunchKernelGGL((ew_cksum_slots_kernel<COPY>), dim3((uint32_t)grid), dim3(kThreads), 0, stream,
+                       (const u32x4 *)((const char *)src + off), (u32x4 *)(COPY ? (char *)dst + off : nullptr), n,
+                       slots);
+    EW_HIP(hipGetLastError());
+    hipLaunchKernelGGL(ew_fold_kernel, dim3((uint32_t)nblk), dim3(kThreads), 0, stream, slots, grid,
+                       out + off / EW_CKSUM_BLOCK);
+    EW_HIP(hipGetLastError());
+  }
+  ew::release_region(region, stream);
+  return EW_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ew_snapshot(const void *src, void *dst, uint64_t nbytes, ew_cksum_t *cksums, void *stream) {
+  if (nbytes == 0) return EW_OK;
+  if (!src || !dst || !cksums) return EW_EINVAL;
+  return launch_cksum<true>(src, dst, nbytes, cksums, (hipStream_t)stream);
+}
+
+int ew_verify(const void *buf, uint64_t nbytes, const ew_cksum_t *expect, ew_cksum_t *got, uint64_t *n_bad,
+              uint64_t *bad_blocks, ew_cksum_t *diffs, uint64_t cap, void *stream) {
+  if (!n_bad) return EW_EINVAL;
+  if (nbytes > 0 && (!buf || !expect || !got)) return EW_EINVAL;
+  if (cap > 0 && (!bad_blocks || !diffs)) return EW_EINVAL;
+  if (nbytes > 0) {
+    const int rc = launch_cksum<false>(buf, nullptr, nbytes, got, (hipStream_t)stream);
+    if (rc != EW_OK) return rc;
+  }
+  const uint64_t nblocks = (nbytes + EW_CKSUM_BLOCK - 1) / EW_CKSUM_BLOCK;
+  hipLaunchKernelGGL(ew_compare_kernel, dim3(1), dim3(kCmpThreads), 0, (hipStream_t)stream, got, expect, nblocks,
+                     n_bad, bad_blocks, diffs, cap);
+  EW_HIP(hipGetLastError());
+  return EW_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,77 @@
+// Device-side building blocks shared by the gfx950 kernels (wave64): 128-bit streaming accesses
+// and the (wrapping 64-bit sum, xor) fold of the per-block checksum.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace ew {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 256;  // four waves of 64; at one 128-bit vector per lane a workgroup moves 4 KiB
+constexpr int kUnroll = 4;     // 128-bit loads in flight per lane where a workgroup moves more than that
+
+// Every byte here is touched exactly once per kernel, so loads and stores carry the nontemporal
+// hint and do not displace the tile tables from the caches.
+__device__ __forceinline__ u32x4 load16(const u32x4 *p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ void store16(u32x4 *p, u32x4 v) { __builtin_nontemporal_store(v, p); }
+
+// Adds the two little-endian 64-bit words of a vector to a lane's running (sum, xor).
+__device__ __forceinline__ void fold(u32x4 v, uint64_t &sum, uint64_t &xr) {
+  const uint64_t w0 = (uint64_t)v.x | ((uint64_t)v.y << 32);
+  const uint64_t w1 = (uint64_t)v.z | ((uint64_t)v.w << 32);
+  sum += w0 + w1;
+  xr ^= w0 ^ w1;
+}
+
+// Wave-wide fold of (sum, xor) with DPP moves: four row_shr steps inside each row of 16 lanes,
+// then row_bcast:15 and row_bcast:31 carry the row totals across rows.  Lanes a move does not
+// reach receive 0, the identity of both operations.  The wave's total ends up in lane 63.
+// (Six cross-lane steps on the VALU; the LDS-crossbar shuffles they replace cost 15 % of a 4 KiB
+// workgroup's run time.)
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint64_t dpp_mov64(uint64_t v) {
+  const uint32_t lo = __builtin_amdgcn_update_dpp(0u, (uint32_t)v, CTRL, ROW_MASK, 0xf, false);
+  const uint32_t hi = __builtin_amdgcn_update_dpp(0u, (uint32_t)(v >> 32), CTRL, ROW_MASK, 0xf, false);
+  return (uint64_t)lo | ((uint64_t)hi << 32);
+}
+constexpr int kWaveFoldLane = 63;
+__device__ __forceinline__ void wave_fold(uint64_t &sum, uint64_t &xr) {
+  sum += dpp_mov64<0x111, 0xf>(sum);  // row_shr:1
+  xr ^= dpp_mov64<0x111, 0xf>(xr);
+  sum += dpp_mov64<0x112, 0xf>(sum);  // row_shr:2
+  xr ^= dpp_mov64<0x112, 0xf>(xr);
+  sum += dpp_mov64<0x114, 0xf>(sum);  // row_shr:4
+  xr ^= dpp_mov64<0x114, 0xf>(xr);
+  sum += dpp_mov64<0x118, 0xf>(sum);  // row_shr:8
+  xr ^= dpp_mov64<0x118, 0xf>(xr);
+  sum += dpp_mov64<0x142, 0xa>(sum);  // row_bcast:15 into rows 1 and 3
+  xr ^= dpp_mov64<0x142, 0xa>(xr);
+  sum += dpp_mov64<0x143, 0xc>(sum);  // row_bcast:31 into rows 2 and 3
+  xr ^= dpp_mov64<0x143, 0xc>(xr);
+}
+
+// Workgroup-wide fold: waves through wave_fold, then the four wave totals through LDS.  The total
+// is valid in thread 0 only.  Each call needs kThreads/64 LDS cells of its own per operand, and a
+// caller that reuses them (a loop) puts a barrier between the calls.
+__device__ __forceinline__ void block_fold(uint64_t &sum, uint64_t &xr, uint64_t *lds_sum, uint64_t *lds_xor) {
+  wave_fold(sum, xr);
+  const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == kWaveFoldLane) {
+    lds_sum[wave] = sum;
+    lds_xor[wave] = xr;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    sum = 0;
+    xr = 0;
+#pragma unroll
+    for (int w = 0; w < kThreads / 64; ++w) {
+      sum += lds_sum[w];
+      xr ^= lds_xor[w];
+    }
+  }
+}
+
+}  // namespace ew

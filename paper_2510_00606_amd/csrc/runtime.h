@@ -1,0 +1,69 @@
+// Host-side state shared by the translation units that launch kernels: HIP error capture, the
+// process-wide launch-shape knobs, the fixed scratch array for per-workgroup checksum slots, and
+// the pointer tables handed to the copy kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <mutex>
+
+#include "plan_internal.h"
+
+namespace ew {
+
+// Records the failing call's message for ew_strerror(EW_EHIP) (per host thread); returns EW_EHIP.
+int hip_fail(hipError_t e, const char *what);
+const char *last_hip_error();
+
+#define EW_HIP(call)                                        \
+  do {                                                      \
+    hipError_t e__ = (call);                                \
+    if (e__ != hipSuccess) return ::ew::hip_fail(e__, #call); \
+  } while (0)
+
+// Launch-shape knobs behind ew_set_param / ew_get_param.
+struct Knobs {
+  int64_t cksum_sub_bytes = 65536;  // streaming checksum kernel: bytes of a block per workgroup pass
+  int64_t cksum_wgs_per_cu = 0;     // streaming checksum kernel: 0 = one workgroup per sub-block,
+                                    // else a persistent grid of this many workgroups per CU
+  int64_t cksum_mode = -1;          // -1 = slot kernel + fold for snapshot, streaming kernel for verify;
+                                    // 0 / 1 force the slot / streaming kernel for both
+  int64_t tile_bytes = 4096;        // default copy tile: 256 lanes x one 128-bit vector
+  int64_t tile_elems = 0;           // > 0 overrides tile_bytes with a size in elements
+  int64_t tile_align_bytes = 128;   // tile cuts fall on multiples of this in the destination (0: off)
+};
+Knobs &knobs();
+
+int num_cus();
+
+// Zero-fill by kernel (safe to record into a HIP graph); nbytes is a multiple of 8.
+int launch_zero(void *p, uint64_t nbytes, hipStream_t stream);
+
+// ---- scratch for per-workgroup checksum slots ---------------------------------------------------
+// A fixed device array, so taking a snapshot never allocates.  It is cut into regions; a stream
+// keeps the region it used last.  When a stream without a region asks for one and all are taken,
+// the least recently used region changes hands, and the new owner's stream is first made to wait
+// (hipStreamWaitEvent, no host blocking) for the event recorded after the region's last use, so
+// two streams never touch a region at once.  A stream under graph capture can only use a region it
+// already owns (its warm-up run claims one).  One region (32 MiB) holds the slots of 2^21
+// workgroups, i.e. 8 GiB of input at 4 KiB per workgroup; longer inputs take several passes.
+constexpr uint32_t kRegions = 4;
+constexpr uint64_t kRegionSlots = 1ull << 21;
+struct Region;
+// All three: the caller holds scratch_mutex() from acquire_region until release_region, so that the
+// kernels of one call reach the stream back to back.  acquire_region returns the region's device
+// address (the region itself through *out), or nullptr when none can be had; release_region is
+// called after the call's last kernel has been enqueued.
+std::mutex &scratch_mutex();
+ew_cksum_t *acquire_region(hipStream_t stream, Region **out);
+void release_region(Region *r, hipStream_t stream);
+
+// ---- pointer tables of the tile-driven kernels, passed by value ----------------------------------
+struct CopyTabs {
+  const char *src[kNumSrc];
+  char *dst[kNumDst];
+};
+// Fills the live-shard and snapshot sources; EW_EINVAL if the plan reads a buffer that is null.
+int fill_tabs(const ew_plan_t *plan, const void *const *old_shards, const void *const *snapshots, CopyTabs &tabs);
+
+}  // namespace ew

@@ -1,0 +1,209 @@
+// Host-side runtime shared by the kernel files: HIP error capture, launch-shape knobs, the scratch
+// regions for per-workgroup checksum slots, and the small C-ABI calls that touch no kernel
+// (ew_set_param, ew_get_param, ew_strerror, ew_version).
+#include "runtime.h"
+
+#include <cstring>
+#include <string>
+
+#include "device_util.h"
+
+namespace ew {
+
+namespace {
+
+thread_local std::string g_hip_error = "no HIP error recorded";
+Knobs g_knobs;
+
+__global__ __launch_bounds__(kThreads) void ew_zero_kernel(uint64_t *p, uint64_t nwords) {
+  const uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i < nwords) p[i] = 0;
+}
+
+// The slots of all regions.  In host code this name is only a handle for hipGetSymbolAddress; every
+// use of the memory goes through the per-device address obtained there.
+__device__ __align__(256) ew_cksum_t g_slot_scratch[kRegions * kRegionSlots];
+
+constexpr int kMaxDevices = 64;
+
+}  // namespace
+
+struct Region {
+  hipStream_t owner = nullptr;
+  bool taken = false;
+  hipEvent_t done = nullptr;  // recorded on the owner's stream after each use
+  bool recorded = false;
+  uint64_t last_use = 0;
+};
+
+namespace {
+
+struct ScratchState {
+  std::mutex mu;
+  ew_cksum_t *base[kMaxDevices] = {nullptr};  // per device: address of that device's copy of the array
+  Region region[kMaxDevices][kRegions];
+  uint64_t clock = 0;
+};
+ScratchState g_scratch;
+
+bool stream_is_capturing(hipStream_t stream) {
+  hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(stream, &st) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  return st != hipStreamCaptureStatusNone;
+}
+
+}  // namespace
+
+int hip_fail(hipError_t e, const char *what) {
+  g_hip_error = std::string(what) + ": " + hipGetErrorString(e);
+  return EW_EHIP;
+}
+
+const char *last_hip_error() { return g_hip_error.c_str(); }
+
+Knobs &knobs() { return g_knobs; }
+
+int num_cus() {
+  static int cached[kMaxDevices] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 256;
+  if (cached[dev] == 0) {
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return 256;
+    cached[dev] = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  }
+  return cached[dev];
+}
+
+int launch_zero(void *p, uint64_t nbytes, hipStream_t stream) {
+  const uint64_t nwords = nbytes / 8;
+  if (nwords == 0) return EW_OK;
+  const uint64_t grid = (nwords + kThreads - 1) / kThreads;
+  if (grid > 0x7fffffffull) return EW_EINVAL;
+  hipLaunchKernelGGL(ew_zero_kernel, dim3((uint32_t)grid), dim3(kThreads), 0, stream, (uint64_t *)p, nwords);
+  EW_HIP(hipGetLastError());
+  return EW_OK;
+}
+
+std::mutex &scratch_mutex() { return g_scratch.mu; }
+
+ew_cksum_t *acquire_region(hipStream_t stream, Region **out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  if (!g_scratch.base[dev]) {
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_slot_scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    g_scratch.base[dev] = (ew_cksum_t *)p;
+  }
+  Region *reg = g_scratch.region[dev];
+  int pick = -1;
+  for (uint32_t r = 0; r < kRegions && pick < 0; ++r)
+    if (reg[r].taken && reg[r].owner == stream) pick = (int)r;
+  for (uint32_t r = 0; r < kRegions && pick < 0; ++r)
+    if (!reg[r].taken) pick = (int)r;
+  if (pick < 0) {
+    if (stream_is_capturing(stream)) return nullptr;  // cannot order a capture after outside work
+    pick = 0;
+    for (uint32_t r = 1; r < kRegions; ++r)
+      if (reg[r].last_use < reg[pick].last_use) pick = (int)r;
+    if (reg[pick].recorded && hipStreamWaitEvent(stream, reg[pick].done, 0) != hipSuccess) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+  }
+  reg[pick].taken = true;
+  reg[pick].owner = stream;
+  *out = &reg[pick];
+  return g_scratch.base[dev] + (uint64_t)pick * kRegionSlots;
+}
+
+void release_region(Region *r, hipStream_t stream) {
+  r->last_use = ++g_scratch.clock;
+  if (stream_is_capturing(stream)) return;  // the graph's own ordering covers replays
+  if (!r->done && hipEventCreateWithFlags(&r->done, hipEventDisableTiming) != hipSuccess) {
+    (void)hipGetLastError();
+    r->done = nullptr;
+    return;
+  }
+  r->recorded = hipEventRecord(r->done, stream) == hipSuccess;
+  if (!r->recorded) (void)hipGetLastError();
+}
+
+int fill_tabs(const ew_plan_t *plan, const void *const *old_shards, const void *const *snapshots, CopyTabs &tabs) {
+  std::memset(&tabs, 0, sizeof(tabs));
+  for (uint32_t j = 0; j < plan->old_dp; ++j) {
+    const void *live = old_shards ? old_shards[j] : nullptr;
+    const void *snap = snapshots ? snapshots[j] : nullptr;
+    if (((plan->live_read >> j) & 1) && !live) return EW_EINVAL;
+    if (((plan->snap_read >> j) & 1) && !snap) return EW_EINVAL;
+    tabs.src[kSrcLive + j] = (const char *)live;
+    tabs.src[kSrcSnap + j] = (const char *)snap;
+  }
+  return EW_OK;
+}
+
+}  // namespace ew
+
+extern "C" {
+
+int ew_set_param(const char *name, int64_t value) {
+  if (!name) return EW_EINVAL;
+  ew::Knobs &k = ew::knobs();
+  if (!std::strcmp(name, "cksum_sub_bytes")) {
+    if (value < 4096 || value > (int64_t)EW_CKSUM_BLOCK || (value & (value - 1))) return EW_EINVAL;
+    k.cksum_sub_bytes = value;
+  } else if (!std::strcmp(name, "cksum_wgs_per_cu")) {
+    if (value < 0 || value > 64) return EW_EINVAL;
+    k.cksum_wgs_per_cu = value;
+  } else if (!std::strcmp(name, "cksum_mode")) {
+    if (value < -1 || value > 1) return EW_EINVAL;
+    k.cksum_mode = value;
+  } else if (!std::strcmp(name, "tile_bytes")) {
+    if (value < 256 || value > (1 << 24) || (value & 15)) return EW_EINVAL;
+    k.tile_bytes = value;
+  } else if (!std::strcmp(name, "tile_elems")) {
+    if (value < 0 || value > (1 << 24)) return EW_EINVAL;
+    k.tile_elems = value;
+  } else if (!std::strcmp(name, "tile_align_bytes")) {
+    if (value < 0 || value > 4096 || (value & (value - 1)) || (value && value < 16)) return EW_EINVAL;
+    k.tile_align_bytes = value;
+  } else {
+    return EW_EINVAL;
+  }
+  return EW_OK;
+}
+
+int64_t ew_get_param(const char *name) {
+  if (!name) return -1;
+  const ew::Knobs &k = ew::knobs();
+  if (!std::strcmp(name, "cksum_sub_bytes")) return k.cksum_sub_bytes;
+  if (!std::strcmp(name, "cksum_wgs_per_cu")) return k.cksum_wgs_per_cu;
+  if (!std::strcmp(name, "cksum_mode")) return k.cksum_mode;
+  if (!std::strcmp(name, "tile_elems")) return k.tile_elems;
+  if (!std::strcmp(name, "tile_bytes")) return k.tile_bytes;
+  if (!std::strcmp(name, "tile_align_bytes")) return k.tile_align_bytes;
+  return -1;
+}
+
+const char *ew_strerror(int code) {
+  switch (code) {
+    case EW_OK: return "ok";
+    case EW_EINVAL: return "invalid argument";
+    case EW_EUNRECOVERABLE:
+      return "unrecoverable: no survivor, or a failed rank's snapshot holder (ring predecessor) failed too";
+    case EW_ENOMEM: return "out of memory";
+    case EW_EHIP: return ew::last_hip_error();
+    case EW_EINFEASIBLE: return "infeasible: no layer partition fits the stages' memory caps";
+    default: return "unknown error code";
+  }
+}
+
+const char *ew_version(void) { return "elaswave-mi355x 0.1 (gfx950)"; }
+
+}  // extern "C"

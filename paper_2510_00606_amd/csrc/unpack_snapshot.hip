@@ -1,0 +1,215 @@
+// Unpack (Live Remap step 3 receiver side and step 4, Sec. 5.2) fused with the snapshot of the new
+// shards (Sec. 5.1): every tile is loaded once and stored twice (new shard and its snapshot copy),
+// and its bytes are folded into the checksum of the 1 MiB block of the NEW shard they land in, so
+// the fresh snapshot of the new layout costs no second read pass.
+//
+// A block's words arrive from many tiles, possibly in pieces that are not word aligned (ragged
+// units); both sum and xor decompose over bytes, so an element at byte offset o of its shard
+// contributes  element << 8*(o mod 8)  to the record of block o >> 20.  Each workgroup writes its
+// tile's (sum, xor) to the tile's slot of a scratch region; the rare tile that straddles a block
+// boundary adds its upper part to the next block's record directly.  ew_fold_tiles_kernel then
+// walks the slots in tile order and adds runs of equal (rank, block) to the records.
+#include <cstring>
+#include <type_traits>
+
+#include "device_util.h"
+#include "runtime.h"
+
+namespace {
+
+using ew::block_fold;
+using ew::CopyTabs;
+using ew::fold;
+using ew::kThreads;
+using ew::load16;
+using ew::store16;
+using ew::TableRef;
+using ew::u32x4;
+
+struct SnapTabs {
+  char *snap[EW_MAX_DP];       // snapshot buffer of each new rank
+  ew_cksum_t *rec[EW_MAX_DP];  // checksum records of each new rank
+  uint32_t nblk[EW_MAX_DP];    // records per rank
+};
+
+__device__ __forceinline__ void add_to_record(ew_cksum_t *rec, uint64_t sum, uint64_t xr) {
+  atomicAdd(reinterpret_cast<unsigned long long *>(&rec->sum), (unsigned long long)sum);
+  atomicXor(reinterpret_cast<unsigned long long *>(&rec->xr), (unsigned long long)xr);
+}
+
+template <int ES>
+__global__ __launch_bounds__(kThreads) void ew_unpack_snap_kernel(TableRef table, uint64_t tile_base, CopyTabs tabs,
+                                                                  SnapTabs st, ew_cksum_t *__restrict__ slots) {
+  __shared__ uint64_t lds_sum[kThreads / 64], lds_xor[kThreads / 64];
+  __shared__ uint64_t lds_sum_hi[kThreads / 64], lds_xor_hi[kThreads / 64];
+  typedef typename std::conditional<ES == 2, uint16_t, uint32_t>::type elem_t;
+  const ew::TileRef tl = ew::decode_tile(table, tile_base + blockIdx.x);
+  const char *s = tabs.src[tl.src_buf] + tl.src_off * ES;
+  const uint64_t dbyte = tl.dst_off * ES;  // byte offset inside the new shard
+  char *d = tabs.dst[tl.dst_buf] + dbyte;
+  char *d2 = st.snap[tl.dst_buf] + dbyte;
+  const uint32_t nbytes = tl.len * ES;
+  const uint64_t boundary = ((dbyte >> 20) + 1) << 20;  // where the next checksum block starts
+  const bool straddle = dbyte + nbytes > boundary;      // wave-uniform, rare
+  uint64_t sum = 0, xr = 0, sum_hi = 0, xr_hi = 0;
+  if ((((uintptr_t)s | (uintptr_t)d | (uintptr_t)d2 | dbyte) & 15u) == 0) {
+    const u32x4 *sv = reinterpret_cast<const u32x4 *>(s);
+    u32x4 *dv = reinterpret_cast<u32x4 *>(d);
+    u32x4 *d2v = reinterpret_cast<u32x4 *>(d2);
+    const uint32_t nvec = nbytes >> 4;
+    for (uint32_t i = threadIdx.x; i < nvec; i += kThreads) {  // one trip for the default 4 KiB tile
+      const u32x4 v = load16(sv + i);
+      store16(dv + i, v);
+      store16(d2v + i, v);
+      if (straddle && dbyte + 16ull * i >= boundary)
+        fold(v, sum_hi, xr_hi);
+      else
+        fold(v, sum, xr);
+    }
+    const uint32_t done = nvec << 4;
+    const uint32_t rem = (nbytes - done) / ES;  // fewer than 16 trailing bytes: whole elements
+    if (threadIdx.x < rem) {
+      const elem_t e = reinterpret_cast<const elem_t *>(s + done)[threadIdx.x];
+      reinterpret_cast<elem_t *>(d + done)[threadIdx.x] = e;
+      reinterpret_cast<elem_t *>(d2 + done)[threadIdx.x] = e;
+      const uint64_t o = dbyte + done + (uint64_t)threadIdx.x * ES;
+      const uint64_t c = (uint64_t)e << (8 * (o & 7));
+      if (o >= boundary) {
+        sum_hi += c;
+        xr_hi ^= c;
+      } else {
+        sum += c;
+        xr ^= c;
+      }
+    }
+  } else {
+    const elem_t *se = reinterpret_cast<const elem_t *>(s);
+    elem_t *de = reinterpret_cast<elem_t *>(d);
+    elem_t *d2e = reinterpret_cast<elem_t *>(d2);
+    for (uint32_t i = threadIdx.x; i < tl.len; i += kThreads) {
+      const elem_t e = se[i];
+      de[i] = e;
+      d2e[i] = e;
+      const uint64_t o = dbyte + (uint64_t)i * ES;
+      const uint64_t c = (uint64_t)e << (8 * (o & 7));
+      if (o >= boundary) {
+        sum_hi += c;
+        xr_hi ^= c;
+      } else {
+        sum += c;
+        xr ^= c;
+      }
+    }
+  }
+  block_fold(sum, xr, lds_sum, lds_xor);
+  if (threadIdx.x == 0) {
+    ew_cksum_t r;
+    r.sum = sum;
+    r.xr = xr;
+    slots[blockIdx.x] = r;
+  }
+  if (straddle) {
+    block_fold(sum_hi, xr_hi, lds_sum_hi, lds_xor_hi);
+    if (threadIdx.x == 0) add_to_record(st.rec[tl.dst_buf] + (boundary >> 20), sum_hi, xr_hi);
+  }
+}
+
+// Lane g adds the slots of tiles [g*per_lane, (g+1)*per_lane) of the pass to the records, one
+// pair of atomics per run of tiles that share (new rank, block): tiles of a segment are adjacent.
+template <int ES>
+__global__ __launch_bounds__(kThreads) void ew_fold_tiles_kernel(TableRef table, uint64_t tile_base, uint64_t ntiles,
+                                                                 uint32_t per_lane, SnapTabs st,
+                                                                 const ew_cksum_t *__restrict__ slots) {
+  const uint64_t g = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+  uint64_t i = g * per_lane;
+  const uint64_t end = (i + per_lane < ntiles) ? i + per_lane : ntiles;
+  if (i >= end) return;
+  uint32_t key_rank = 0;
+  uint64_t key_blk = 0, sum = 0, xr = 0;
+  bool open = false;
+  for (; i < end; ++i) {
+    const ew::TileRef tl = ew::decode_tile(table, tile_base + i);
+    const uint64_t blk = (tl.dst_off * ES) >> 20;
+    if (open && (tl.dst_buf != key_rank || blk != key_blk)) {
+      add_to_record(st.rec[key_rank] + key_blk, sum, xr);
+      sum = 0;
+      xr = 0;
+    }
+    open = true;
+    key_rank = tl.dst_buf;
+    key_blk = blk;
+    const ew_cksum_t r = slots[i];
+    sum += r.sum;
+    xr ^= r.xr;
+  }
+  add_to_record(st.rec[key_rank] + key_blk, sum, xr);
+}
+
+// Zeroes every new rank's records: blockIdx.y = rank, 2 words per record.
+__global__ __launch_bounds__(kThreads) void ew_zero_records_kernel(SnapTabs st) {
+  const uint32_t k = blockIdx.y;
+  const uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i < 2ull * st.nblk[k]) reinterpret_cast<uint64_t *>(st.rec[k])[i] = 0;
+}
+
+template <int ES>
+int launch_pass(const ew::TileTable &tt, uint64_t t0, uint64_t n, const CopyTabs &tabs, const SnapTabs &st,
+                ew_cksum_t *slots, hipStream_t stream) {
+  constexpr uint32_t kTilesPerLane = 16;
+  const uint64_t fold_grid = ((n + kTilesPerLane - 1) / kTilesPerLane + kThreads - 1) / kThreads;
+  hipLaunchKernelGGL(ew_unpack_snap_kernel<ES>, dim3((uint32_t)n), dim3(kThreads), 0, stream, tt.dev, t0, tabs, st,
+                     slots);
+  EW_HIP(hipGetLastError());
+  hipLaunchKernelGGL(ew_fold_tiles_kernel<ES>, dim3((uint32_t)fold_grid), dim3(kThreads), 0, stream, tt.dev, t0, n,
+                     kTilesPerLane, st, slots);
+  EW_HIP(hipGetLastError());
+  return EW_OK;
+}
+
+}  // namespace
+
+extern "C" int ew_unpack_snapshot(const ew_plan_t *plan, const void *stage, const void *const *old_shards,
+                                  const void *const *snapshots, void *const *new_shards, void *const *new_snapshots,
+                                  ew_cksum_t *const *new_cksums, uint32_t elem_size, void *stream_) {
+  if (!plan || !plan->uploaded || (elem_size != 2 && elem_size != 4)) return EW_EINVAL;
+  const int e = elem_size == 4 ? 1 : 0;
+  const ew::TileTable &tt = plan->tables[1][e];
+  if (tt.ntiles == 0) return EW_OK;
+  if (!new_shards || !new_snapshots || !new_cksums) return EW_EINVAL;
+  if (plan->stage_len > 0 && !stage) return EW_EINVAL;
+  if ((uint64_t)plan->tile_elems[e] * elem_size > EW_CKSUM_BLOCK) return EW_EINVAL;  // a tile spans <= 2 blocks
+  hipStream_t stream = (hipStream_t)stream_;
+  CopyTabs tabs;
+  const int rc = ew::fill_tabs(plan, old_shards, snapshots, tabs);
+  if (rc != EW_OK) return rc;
+  tabs.src[ew::kSrcStage] = (const char *)stage;
+  SnapTabs st;
+  std::memset(&st, 0, sizeof(st));
+  uint32_t max_blk = 0;
+  for (uint32_t k = 0; k < plan->new_dp; ++k) {
+    if (plan->new_len[k] == 0) continue;
+    if (!new_shards[k] || !new_snapshots[k] || !new_cksums[k]) return EW_EINVAL;
+    const uint64_t nblk = (plan->new_len[k] * elem_size + EW_CKSUM_BLOCK - 1) / EW_CKSUM_BLOCK;
+    if (nblk > 0x3fffffffull) return EW_EINVAL;  // 2 words per record must fit the zero-fill grid
+    tabs.dst[k] = (char *)new_shards[k];
+    st.snap[k] = (char *)new_snapshots[k];
+    st.rec[k] = new_cksums[k];
+    st.nblk[k] = (uint32_t)nblk;
+    if (st.nblk[k] > max_blk) max_blk = st.nblk[k];
+  }
+  std::lock_guard<std::mutex> lock(ew::scratch_mutex());
+  ew::Region *region = nullptr;
+  ew_cksum_t *slots = ew::acquire_region(stream, &region);
+  if (!slots) return EW_ENOMEM;  // only for a capturing stream that owns no region
+  hipLaunchKernelGGL(ew_zero_records_kernel, dim3((2 * max_blk + kThreads - 1) / kThreads, plan->new_dp),
+                     dim3(kThreads), 0, stream, st);
+  EW_HIP(hipGetLastError());
+  for (uint64_t t0 = 0; t0 < tt.ntiles; t0 += ew::kRegionSlots) {
+    const uint64_t n = tt.ntiles - t0 < ew::kRegionSlots ? tt.ntiles - t0 : ew::kRegionSlots;
+    const int prc = elem_size == 2 ? launch_pass<2>(tt, t0, n, tabs, st, slots, stream)
+                                   : launch_pass<4>(tt, t0, n, tabs, st, slots, stream);
+    if (prc != EW_OK) return prc;
+  }
+  ew::release_region(region, stream);
+  return EW_OK;
+}
