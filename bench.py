@@ -41,8 +41,8 @@ KERNEL_OF = {"snapshot_old": "ew_cksum_slots_kernel<copy> (+ ew_fold_kernel) = e
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="7b_stage", choices=["tiny", "7b_stage", "13b_stage", "70b_stage"],
                     help="70b_stage does not fit 288 GB with all four arrays resident: it is measured one "
                          "array at a time (each array resident before its own timed steps) and summed")
