@@ -88,6 +88,7 @@ void release_tables(ew_plan_t *plan) {
   if (plan->host_buf) (void)hipHostFree(plan->host_buf);
   plan->dev_buf = plan->host_buf = nullptr;
   plan->uploaded = false;
+  plan->device = -1;
   for (int w = 0; w < 2; ++w)
     for (int e = 0; e < 2; ++e) plan->tables[w][e] = ew::TileTable();
 }
@@ -158,6 +159,11 @@ int ew_plan_upload(ew_plan_t *plan, uint32_t tile_elems, void *stream) {
     return EW_ENOMEM;
   }
   if (bytes > 0) {
+    if (hipGetDevice(&plan->device) != hipSuccess) {
+      (void)hipGetLastError();
+      plan->device = -1;
+      return EW_EINVAL;
+    }
     if (hipHostMalloc(&plan->host_buf, bytes, hipHostMallocDefault) != hipSuccess ||
         hipMalloc(&plan->dev_buf, bytes) != hipSuccess) {
       (void)hipGetLastError();
@@ -197,7 +203,7 @@ int ew_plan_upload(ew_plan_t *plan, uint32_t tile_elems, void *stream) {
 
 int ew_pack(const ew_plan_t *plan, const void *const *old_shards, const void *const *snapshots, void *stage,
             uint32_t elem_size, void *stream) {
-  if (!plan || !plan->uploaded || (elem_size != 2 && elem_size != 4)) return EW_EINVAL;
+  if (!ew::tables_usable(plan) || (elem_size != 2 && elem_size != 4)) return EW_EINVAL;
   const ew::TileTable &tt = plan->tables[0][elem_size == 4 ? 1 : 0];
   if (tt.ntiles == 0) return EW_OK;
   if (!stage) return EW_EINVAL;
@@ -210,7 +216,7 @@ int ew_pack(const ew_plan_t *plan, const void *const *old_shards, const void *co
 
 int ew_unpack(const ew_plan_t *plan, const void *stage, const void *const *old_shards, const void *const *snapshots,
               void *const *new_shards, uint32_t elem_size, void *stream) {
-  if (!plan || !plan->uploaded || (elem_size != 2 && elem_size != 4)) return EW_EINVAL;
+  if (!ew::tables_usable(plan) || (elem_size != 2 && elem_size != 4)) return EW_EINVAL;
   const ew::TileTable &tt = plan->tables[1][elem_size == 4 ? 1 : 0];
   if (tt.ntiles == 0) return EW_OK;
   if (!new_shards) return EW_EINVAL;

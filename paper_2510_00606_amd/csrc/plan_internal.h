@@ -134,6 +134,7 @@ struct ew_plan_s {
   std::vector<ew_seg_t> segs;
   // device side (filled by ew_plan_upload)
   bool uploaded = false;
+  int device = -1;  // device that holds dev_buf; pack / unpack refuse to launch on another
   uint32_t tile_elems[2] = {0, 0};              // [0]: 2-byte elements, [1]: 4-byte elements
   ew::TileTable tables[2][2];                   // [which: 0 pack, 1 unpack][elem size index]
   void *host_buf = nullptr;                     // pinned staging copy, kept until the plan is freed

@@ -63,6 +63,8 @@ struct CopyTabs {
   const char *src[kNumSrc];
   char *dst[kNumDst];
 };
+// True if the plan's tables are uploaded and live on the current device.
+bool tables_usable(const ew_plan_t *plan);
 // Fills the live-shard and snapshot sources; EW_EINVAL if the plan reads a buffer that is null.
 int fill_tabs(const ew_plan_t *plan, const void *const *old_shards, const void *const *snapshots, CopyTabs &tabs);
 

@@ -103,7 +103,10 @@ ew_cksum_t *acquire_region(hipStream_t stream, Region **out) {
   }
   Region *reg = g_scratch.region[dev];
   int pick = -1;
-  for (uint32_t r = 0; r < kRegions && pick < 0; ++r)
+  // hipStreamPerThread names a different stream in every host thread, so it never owns a region:
+  // each of its calls goes through the event-ordered handover below
+  const bool ownable = stream != hipStreamPerThread;
+  for (uint32_t r = 0; r < kRegions && pick < 0 && ownable; ++r)
     if (reg[r].taken && reg[r].owner == stream) pick = (int)r;
   for (uint32_t r = 0; r < kRegions && pick < 0; ++r)
     if (!reg[r].taken) pick = (int)r;
@@ -129,10 +132,24 @@ void release_region(Region *r, hipStream_t stream) {
   if (!r->done && hipEventCreateWithFlags(&r->done, hipEventDisableTiming) != hipSuccess) {
     (void)hipGetLastError();
     r->done = nullptr;
-    return;
   }
-  r->recorded = hipEventRecord(r->done, stream) == hipSuccess;
-  if (!r->recorded) (void)hipGetLastError();
+  r->recorded = r->done && hipEventRecord(r->done, stream) == hipSuccess;
+  if (!r->recorded) {
+    // no event to hand the region over with: leave it idle instead
+    (void)hipGetLastError();
+    (void)hipStreamSynchronize(stream);
+  }
+}
+
+bool tables_usable(const ew_plan_t *plan) {
+  if (!plan || !plan->uploaded) return false;
+  if (plan->device < 0) return true;  // nothing was uploaded: all tables are empty
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  return dev == plan->device;
 }
 
 int fill_tabs(const ew_plan_t *plan, const void *const *old_shards, const void *const *snapshots, CopyTabs &tabs) {

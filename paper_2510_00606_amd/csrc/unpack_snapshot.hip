@@ -171,7 +171,7 @@ int launch_pass(const ew::TileTable &tt, uint64_t t0, uint64_t n, const CopyTabs
 extern "C" int ew_unpack_snapshot(const ew_plan_t *plan, const void *stage, const void *const *old_shards,
                                   const void *const *snapshots, void *const *new_shards, void *const *new_snapshots,
                                   ew_cksum_t *const *new_cksums, uint32_t elem_size, void *stream_) {
-  if (!plan || !plan->uploaded || (elem_size != 2 && elem_size != 4)) return EW_EINVAL;
+  if (!ew::tables_usable(plan) || (elem_size != 2 && elem_size != 4)) return EW_EINVAL;
   const int e = elem_size == 4 ? 1 : 0;
   const ew::TileTable &tt = plan->tables[1][e];
   if (tt.ntiles == 0) return EW_OK;

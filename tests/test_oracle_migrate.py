@@ -102,3 +102,36 @@ def test_interleaved_rank_keeps_piece_j_of_every_layer():
     for j in range(D):
         assert np.array_equal(ns[j], s_sh[j][:3 * per])
         assert np.array_equal(nd[j], np.concatenate([s_sh[j][3 * per:], d_sh[j]]))
+
+
+def test_hand_worked_migration_of_unequal_layers():
+    # Stage S holds layers of 16, 24, 32 elements, stage S+1 layers of 8 and 40; D = 2; element i of
+    # layer l carries the value 1000*l + i.  Granule floor split of a layer of L elements over 2 ranks:
+    # 16 -> 8|8, 24 -> 8|16, 32 -> 16|16, 8 -> 0|8, 40 -> 16|24.  All expected arrays below are written
+    # out by hand from those cuts, none comes from the oracle.
+    def lay(l, a, b):
+        return [1000 * l + i for i in range(a, b)]
+    src, dst = np.asarray([0, 16, 40, 72]), np.asarray([0, 8, 48])
+    s_sh = [np.asarray(lay(0, 0, 8) + lay(1, 0, 8) + lay(2, 0, 16)), np.asarray(lay(0, 8, 16) + lay(1, 8, 24) + lay(2, 16, 32))]
+    d_sh = [np.asarray(lay(4, 0, 16)), np.asarray(lay(3, 0, 8) + lay(4, 16, 40))]
+    # the LAST layer of stage S becomes the FIRST layer of stage S+1
+    new_src, new_dst, cut = migrate.moved_starts(src, dst, 1)
+    assert new_src.tolist() == [0, 16, 40] and new_dst.tolist() == [0, 32, 40, 80] and cut == 40
+    ns, nd = migrate.migrate(s_sh, d_sh, src, dst, 2, INTERLEAVED, 1)
+    assert ns[0].tolist() == lay(0, 0, 8) + lay(1, 0, 8) and ns[1].tolist() == lay(0, 8, 16) + lay(1, 8, 24)
+    assert nd[0].tolist() == lay(2, 0, 16) + lay(4, 0, 16)
+    assert nd[1].tolist() == lay(2, 16, 32) + lay(3, 0, 8) + lay(4, 16, 40)
+    # two layers move: they keep their order in front of stage S+1's own layers
+    new_src, new_dst, cut = migrate.moved_starts(src, dst, 2)
+    assert new_src.tolist() == [0, 16] and new_dst.tolist() == [0, 24, 56, 64, 104] and cut == 16
+    ns, nd = migrate.migrate(s_sh, d_sh, src, dst, 2, INTERLEAVED, 2)
+    assert ns[0].tolist() == lay(0, 0, 8) and ns[1].tolist() == lay(0, 8, 16)
+    assert nd[0].tolist() == lay(1, 0, 8) + lay(2, 0, 16) + lay(4, 0, 16)
+    assert nd[1].tolist() == lay(1, 8, 24) + lay(2, 16, 32) + lay(3, 0, 8) + lay(4, 16, 40)
+    # contiguous rule, one layer moves: a stage's whole array gets one granule floor split, before
+    # 72 -> 32|40 and 48 -> 24|24, afterwards 40 -> 16|24 and 80 -> 40|40
+    cs = [np.asarray(lay(0, 0, 16) + lay(1, 0, 16)), np.asarray(lay(1, 16, 24) + lay(2, 0, 32))]       # 72 -> 32|40
+    cd = [np.asarray(lay(3, 0, 8) + lay(4, 0, 16)), np.asarray(lay(4, 16, 40))]                       # 48 -> 24|24
+    ns, nd = migrate.migrate(cs, cd, src, dst, 2, CONTIGUOUS, 1)
+    assert ns[0].tolist() == lay(0, 0, 16) and ns[1].tolist() == lay(1, 0, 24)                        # 40 -> 16|24
+    assert nd[0].tolist() == lay(2, 0, 32) + lay(3, 0, 8) and nd[1].tolist() == lay(4, 0, 40)         # 80 -> 40|40

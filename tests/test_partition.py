@@ -34,6 +34,11 @@ def test_oracle_closed_forms():
     t, mem = tables(6, 3, [1, 1, 10, 1, 1, 1], [1] * 6)
     cost, b = partition.best_partition(6, 3, t, mem, [6] * 3)
     assert cost == 10.0 and partition.partition_cost(6, 3, t, mem, [6] * 3, b) == 10.0
+    # unequal stages: stage 1 at half speed, four unit layers: (1,3) costs 6, (2,2) 4, (3,1) 3
+    t, mem = tables(4, 2, [1.0] * 4, [1.0] * 4, stage_speed=[1.0, 0.5])
+    assert partition.best_partition(4, 2, t, mem, [4, 4]) == (3.0, [3])
+    # ... and with stage 0 capped at two layers the best left is (2,2)
+    assert partition.best_partition(4, 2, t, mem, [2, 4]) == (4.0, [2])
     # a cap of one layer per stage with more layers than stages: infeasible
     t, mem = tables(5, 3, [1] * 5, [1] * 5)
     assert partition.best_partition(5, 3, t, mem, [1, 1, 1]) == (math.inf, None)
