@@ -286,6 +286,26 @@ def test_snapshot_on_many_streams():
         assert np.array_equal(ck[i].cpu().numpy().view(np.uint64), checksum.block_checksums(raw[i]))
 
 
+def test_snapshot_on_the_per_thread_stream():
+    """The per-thread default stream is one handle value for a different stream in every host
+    thread, so it must never be taken for the owner of a scratch region: eight calls in a row on it
+    (twice the number of regions) go through the event-ordered handover and give the oracle's result."""
+    HIP_STREAM_PER_THREAD = 2
+    rng = np.random.default_rng(78)
+    nbytes = 3 * MIB + 100
+    raw = [rng.integers(0, 256, nbytes, dtype=np.uint8) for _ in range(8)]
+    src = [torch.from_numpy(r).to(DEV) for r in raw]
+    dst = [torch.zeros(nbytes, dtype=torch.uint8, device=DEV) for _ in raw]
+    ck = [torch.zeros((ew.num_blocks(nbytes), 2), dtype=torch.int64, device=DEV) for _ in raw]
+    torch.cuda.synchronize()
+    for i in range(len(raw)):
+        ew.ew_snapshot(src[i], dst[i], nbytes, ck[i], HIP_STREAM_PER_THREAD)
+    torch.cuda.synchronize()
+    for i in range(len(raw)):
+        assert np.array_equal(dst[i].cpu().numpy(), raw[i])
+        assert np.array_equal(ck[i].cpu().numpy().view(np.uint64), checksum.block_checksums(raw[i]))
+
+
 @pytest.mark.timeout(600)
 def test_snapshot_longer_than_one_scratch_pass():
     """17 GiB + ragged tail: three passes over the 8 GiB scratch region."""
