@@ -220,6 +220,10 @@ def test_reshard_small_exhaustive(elem_size):
     (5, 9, 0b10101, 800_000, 800_000),        # one unit, two failures, growth
     (3, 2, 0b111, 2_600_000, 99_992),         # new shards of several checksum blocks, tiles straddling them
     (2, 3, 0b10, 1_900_003, 70_001),          # ragged units: words split between segments
+    (64, 63, (1 << 63) - 1, 64 * 63 * 8 * 3 + 40, 64 * 63 * 8),   # the largest degree, last rank failed
+    (64, 32, 0x5555555555555555, 1_000_000, 40_000),               # every second rank failed: 32 snapshots in use
+    (1, 64, 0b1, 300_000, 30_000),            # scatter from one rank to the largest degree
+    (64, 1, (1 << 64) - 1, 300_000, 30_000),  # gather from the largest degree
 ])
 def test_reshard_medium(case, elem_size):
     rng = np.random.default_rng(hash(case) & 0xFFFF)
