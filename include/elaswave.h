@@ -220,8 +220,11 @@ int ew_unpack_snapshot(const ew_plan_t *plan, const void *stage, const void *con
  * more than 4 streams take turns, the least recently used region changes hands and the new stream
  * is made to wait (on the device, not the host) for that region's last use.  Buffers that are not
  * 16-byte aligned, and a stream under graph capture that owns no region yet (run the calls once on
- * it before capturing), use a slower kernel that needs no scratch.  Calls may be issued from
- * several host threads. */
+ * it before capturing), use a slower kernel that needs no scratch.  A region that a captured graph
+ * uses stays with the capturing stream for good (the graph's replays are invisible to the
+ * library): replay such a graph on the stream it was captured on, or ordered after that stream's
+ * other calls, and capture on at most 4 streams per device.  Calls may be issued from several
+ * host threads. */
 int ew_snapshot(const void *src, void *dst, uint64_t nbytes, ew_cksum_t *cksums, void *stream);
 
 /* ---- Integrity check of stored bytes (Live Remap step 1) ----------------------------------

@@ -33,6 +33,7 @@ struct Region {
   bool taken = false;
   hipEvent_t done = nullptr;  // recorded on the owner's stream after each use
   bool recorded = false;
+  bool in_graph = false;  // some captured graph uses it: its replays are invisible here, so it never changes hands
   uint64_t last_use = 0;
 };
 
@@ -112,9 +113,9 @@ ew_cksum_t *acquire_region(hipStream_t stream, Region **out) {
     if (!reg[r].taken) pick = (int)r;
   if (pick < 0) {
     if (stream_is_capturing(stream)) return nullptr;  // cannot order a capture after outside work
-    pick = 0;
-    for (uint32_t r = 1; r < kRegions; ++r)
-      if (reg[r].last_use < reg[pick].last_use) pick = (int)r;
+    for (uint32_t r = 0; r < kRegions; ++r)
+      if (!reg[r].in_graph && (pick < 0 || reg[r].last_use < reg[pick].last_use)) pick = (int)r;
+    if (pick < 0) return nullptr;  // every region belongs to a captured graph
     if (reg[pick].recorded && hipStreamWaitEvent(stream, reg[pick].done, 0) != hipSuccess) {
       (void)hipGetLastError();
       return nullptr;
@@ -128,7 +129,10 @@ ew_cksum_t *acquire_region(hipStream_t stream, Region **out) {
 
 void release_region(Region *r, hipStream_t stream) {
   r->last_use = ++g_scratch.clock;
-  if (stream_is_capturing(stream)) return;  // the graph's own ordering covers replays
+  if (stream_is_capturing(stream)) {  // the graph's own ordering covers its replays on one stream
+    r->in_graph = true;
+    return;
+  }
   if (!r->done && hipEventCreateWithFlags(&r->done, hipEventDisableTiming) != hipSuccess) {
     (void)hipGetLastError();
     r->done = nullptr;
