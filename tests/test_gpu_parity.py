@@ -142,8 +142,14 @@ def test_verify_many_flips_ordered_and_capped():
 
 
 # ------------------------------------------------------------------ pack / unpack
-def reshard_case(old_dp, new_dp, mask, numel, chunk, elem_size, rng, tile_elems=0):
-    starts = layout.unit_starts(numel, chunk)
+def reshard_case(old_dp, new_dp, mask, numel, chunk, elem_size, rng, tile_elems=0, starts=None):
+    """Uniform chunk, or explicit unit boundaries `starts` (then numel and chunk are ignored)."""
+    explicit = starts is not None
+    if explicit:
+        starts = np.asarray(starts, dtype=np.int64)
+        numel = int(starts[-1])
+    else:
+        starts = layout.unit_starts(numel, chunk)
     alive = layout.alive_list(old_dp, mask)
     lens = layout.shard_lengths(starts, old_dp)
     data = random_shards(lens, elem_size, rng)   # the true content of every old rank's partition
@@ -156,7 +162,7 @@ def reshard_case(old_dp, new_dp, mask, numel, chunk, elem_size, rng, tile_elems=
     # device: failed ranks' live shards are poisoned, alive ranks have no snapshot at all
     old_dev = [to_dev(d if alive[j] else np.full_like(d, poison), elem_size) for j, d in enumerate(data)]
     snap_dev = [None if alive[j] else to_dev(d, elem_size) for j, d in enumerate(data)]
-    plan = ew.ew_plan(old_dp, new_dp, mask, numel, chunk)
+    plan = ew.ew_plan_bounds(old_dp, new_dp, mask, starts) if explicit else ew.ew_plan(old_dp, new_dp, mask, numel, chunk)
     stage, new = run_reshard(plan, old_dev, snap_dev, elem_size, tile_elems)
 
     assert plan.stage_len == len(want_stage)
@@ -238,6 +244,39 @@ def test_reshard_launch_shapes(tile_elems, align):
     for es in (2, 4):
         reshard_case(8, 7, 0xFF & ~(1 << 5), 3_000_000 + 8 * 37, 262144, es, rng, tile_elems)
         reshard_case(6, 4, 0b111011, 999_999, 10_007, es, rng, tile_elems)
+
+
+def random_unit_lengths(rng):
+    """A mix of what real boundary lists contain: runs of equal units, tensors of odd sizes, empty
+    and tiny units, lengths that are not multiples of the 8-element granule."""
+    lens = []
+    for _ in range(int(rng.integers(1, 9))):
+        kind = int(rng.integers(0, 6))
+        if kind == 0:
+            lens += [int(rng.integers(1, 40)) * 8 * int(rng.integers(1, 200))] * int(rng.integers(2, 12))   # a run
+        elif kind == 1:
+            lens.append(int(rng.integers(0, 60)))                       # tiny or empty
+        elif kind == 2:
+            lens.append(int(rng.integers(1, 30_000)))                   # ragged
+        elif kind == 3:
+            lens.append(8 * int(rng.integers(1, 40_000)))               # granule multiple, several tiles
+        elif kind == 4:
+            lens += [int(rng.integers(1, 2_000))] * int(rng.integers(2, 6))   # a run of ragged units
+        else:
+            lens.append(1024 * int(rng.integers(1, 300)))               # tile multiple
+    return lens
+
+
+@pytest.mark.parametrize("seed", range(48))
+def test_reshard_random_unit_boundaries(seed):
+    rng = np.random.default_rng(1000 + seed)
+    old_dp, new_dp = int(rng.integers(1, 10)), int(rng.integers(1, 10))
+    masks = recoverable_masks(old_dp)
+    mask = masks[int(rng.integers(0, len(masks)))]
+    starts = np.concatenate([[0], np.cumsum(random_unit_lengths(rng))])
+    ew.ew_set_param("tile_align_bytes", int(rng.choice([0, 16, 128, 256])))
+    tile_elems = int(rng.choice([0, 0, 256, 1024, 3000]))
+    reshard_case(old_dp, new_dp, mask, None, None, 2 + 2 * (seed & 1), rng, tile_elems, starts=starts)
 
 
 def test_null_buffers_are_rejected():
