@@ -349,6 +349,43 @@ def test_snapshot_on_the_per_thread_stream():
         assert np.array_equal(ck[i].cpu().numpy().view(np.uint64), checksum.block_checksums(raw[i]))
 
 
+def test_snapshot_from_several_host_threads():
+    """Six host threads, each with a stream of its own, issue snapshots at the same time (ctypes
+    releases the interpreter lock during a call): more threads than scratch regions, so regions
+    change hands while other threads are inside the library.  Every result is the oracle's."""
+    import threading
+    rng = np.random.default_rng(79)
+    n_threads, reps = 6, 12
+    nbytes = [2 * MIB + 4096 * i + 7 * i for i in range(n_threads)]
+    raw = [rng.integers(0, 256, n, dtype=np.uint8) for n in nbytes]
+    src = [torch.from_numpy(r).to(DEV) for r in raw]
+    dst = [torch.zeros(n, dtype=torch.uint8, device=DEV) for n in nbytes]
+    ck = [torch.zeros((ew.num_blocks(n), 2), dtype=torch.int64, device=DEV) for n in nbytes]
+    streams = [torch.cuda.Stream() for _ in range(n_threads)]
+    torch.cuda.synchronize()
+    errors = []
+    go = threading.Barrier(n_threads)
+
+    def work(i):
+        try:
+            go.wait()
+            for _ in range(reps):
+                ew.ew_snapshot(src[i], dst[i], nbytes[i], ck[i], streams[i].cuda_stream)
+        except Exception as e:   # reported by the main thread
+            errors.append((i, repr(e)))
+
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(n_threads)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for i in range(n_threads):
+        assert np.array_equal(dst[i].cpu().numpy(), raw[i])
+        assert np.array_equal(ck[i].cpu().numpy().view(np.uint64), checksum.block_checksums(raw[i]))
+
+
 @pytest.mark.timeout(600)
 def test_snapshot_longer_than_one_scratch_pass():
     """17 GiB + ragged tail: three passes over the 8 GiB scratch region."""
