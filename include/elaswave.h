@@ -237,6 +237,16 @@ int ew_verify(const void *buf, uint64_t nbytes, const ew_cksum_t *expect, ew_cks
               uint64_t *n_bad, uint64_t *bad_blocks, ew_cksum_t *diffs, uint64_t cap,
               void *stream);
 
+/* What a bad block's differences say about the damage (host, pure arithmetic).  One flipped bit
+ * at byte offset o, bit b of a buffer changes exactly one 64-bit word of block o >> 20 by
+ * +-2^(8*(o mod 8) + b): the xor difference is one-hot and the sum difference is plus or minus the
+ * same value mod 2^64.  Returns 1 if *diff (one record of ew_verify's diffs[], copied to the host)
+ * has that form and then writes the bit lane 8*(o mod 8) + b (0..63) to *lane and +1 (the bit
+ * reads 1 now and was 0 when the checksum was taken) or -1 to *direction; returns 0 otherwise
+ * (several bits, or none).  In lane 63 both directions give the same differences: +1 is reported.
+ * Which word of the block was hit cannot be told from (sum, xor). */
+int ew_single_bit_flip(const ew_cksum_t *diff, uint32_t *lane, int32_t *direction);
+
 /* ---- Gradient-shipping snapshot (Sec. 5.1, Fig. 6) --------------------------------------------
  * The paper keeps worker i's snapshot of worker (i+1)'s optimizer partition current without copying
  * the Adam state every step: worker i+1 ships the GRADIENT shard of its partition (device to device,

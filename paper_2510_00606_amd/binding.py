@@ -70,6 +70,7 @@ _SIGNATURES = {
     "ew_snapshot": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]),
     "ew_verify": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                             C.c_uint64, C.c_void_p]),
+    "ew_single_bit_flip": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint32), C.POINTER(C.c_int32)]),
     "ew_adam_hyper": (C.c_int, [C.c_float, C.c_float, C.c_float, C.c_float, C.c_float, C.c_uint64, C.c_void_p]),
     "ew_adam_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint64,
                                C.c_void_p, C.c_void_p]),
@@ -340,6 +341,15 @@ def ew_verify(buf, nbytes: int, expect, got, n_bad, bad_blocks, diffs, cap: int,
             raise ValueError(f"{name} holds {n} bytes, call needs {need}")
     _check(lib().ew_verify(_ptr(buf), nbytes, _ptr(expect), _ptr(got), _ptr(n_bad), _ptr(bad_blocks), _ptr(diffs),
                            cap, _stream(stream)), "ew_verify")
+
+
+def ew_single_bit_flip(sum_diff: int, xor_diff: int):
+    """(lane, direction) if the differences of one bad block are those of one flipped bit, else None."""
+    rec = (C.c_uint64 * 2)(sum_diff & ((1 << 64) - 1), xor_diff & ((1 << 64) - 1))
+    lane, direction = C.c_uint32(), C.c_int32()
+    if lib().ew_single_bit_flip(C.addressof(rec), C.byref(lane), C.byref(direction)):
+        return lane.value, direction.value
+    return None
 
 
 class AdamHyper(C.Structure):

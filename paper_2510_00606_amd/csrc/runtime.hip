@@ -212,6 +212,22 @@ int64_t ew_get_param(const char *name) {
   return -1;
 }
 
+int ew_single_bit_flip(const ew_cksum_t *diff, uint32_t *lane, int32_t *direction) {
+  if (!diff || !lane || !direction) return 0;
+  const uint64_t x = diff->xr;
+  if (x == 0 || (x & (x - 1)) != 0) return 0;  // not one-hot
+  int32_t dir;
+  if (diff->sum == x)
+    dir = 1;
+  else if (diff->sum == (uint64_t)0 - x)
+    dir = -1;  // (bit 63: +x and -x coincide and read as +1)
+  else
+    return 0;
+  *lane = (uint32_t)__builtin_ctzll(x);
+  *direction = dir;
+  return 1;
+}
+
 const char *ew_strerror(int code) {
   switch (code) {
     case EW_OK: return "ok";

@@ -203,5 +203,7 @@ def test_7b_rank_snapshot_and_bit_flip():
             hb[o] ^= np.uint8(1 << bit)
             o_bad, o_diffs = checksum.verify(hb, want)
             assert o_bad.tolist() == [o >> 20] and np.array_equal(o_diffs[0], d)
+            lane, direction = ew.ew_single_bit_flip(int(d[0]), int(d[1]))   # "locate": block above, bit lane here
+            assert lane == 8 * (o % 8) + bit and direction == (1 if (hb[o] >> bit) & 1 or lane == 63 else -1)
         del src, snap
         free()
