@@ -486,7 +486,7 @@ def test_random_boundaries_and_memberships_match_the_oracle():
         lens = draw(st.lists(st.sampled_from([0, 1, 7, 8, 16, 24, 100, 264, 1000]), min_size=0, max_size=12))
         return old_dp, new_dp, sum(1 << j for j, a in enumerate(alive) if a), lens
 
-    @settings(max_examples=150, deadline=None)
+    @settings(max_examples=150, deadline=None, derandomize=True, database=None)
     @given(cases())
     def run(case):
         old_dp, new_dp, mask, lens = case
