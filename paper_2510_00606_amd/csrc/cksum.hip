@@ -243,9 +243,8 @@ int launch_cksum(const void *src, void *dst, uint64_t nbytes, ew_cksum_t *out, h
   const int64_t mode = ew::knobs().cksum_mode >= 0 ? ew::knobs().cksum_mode : (COPY ? 0 : 1);
   if (!aligned || mode != 0) return launch_cksum_streaming<COPY>(src, dst, nbytes, out, stream);
   // the (slot kernel, fold kernel) pairs of one call must reach the stream back to back
-  std::lock_guard<std::mutex> lock(ew::scratch_mutex());
-  ew::Region *region = nullptr;
-  ew_cksum_t *slots = ew::acquire_region(stream, &region);
+  ew::ScratchLease lease(stream);
+  ew_cksum_t *slots = lease.slots();
   if (!slots) return launch_cksum_streaming<COPY>(src, dst, nbytes, out, stream);  // needs no scratch
   constexpr uint64_t kPassBytes = ew::kRegionSlots * 4096;
   for (uint64_t off = 0; off < nbytes; off += kPassBytes) {
@@ -262,7 +261,6 @@ int launch_cksum(const void *src, void *dst, uint64_t nbytes, ew_cksum_t *out, h
                        out + off / EW_CKSUM_BLOCK);
     EW_HIP(hipGetLastError());
   }
-  ew::release_region(region, stream);
   return EW_OK;
 }
 

@@ -51,13 +51,25 @@ int launch_zero(void *p, uint64_t nbytes, hipStream_t stream);
 constexpr uint32_t kRegions = 4;
 constexpr uint64_t kRegionSlots = 1ull << 21;
 struct Region;
-// All three: the caller holds scratch_mutex() from acquire_region until release_region, so that the
-// kernels of one call reach the stream back to back.  acquire_region returns the region's device
-// address (the region itself through *out), or nullptr when none can be had; release_region is
-// called after the call's last kernel has been enqueued.
-std::mutex &scratch_mutex();
-ew_cksum_t *acquire_region(hipStream_t stream, Region **out);
-void release_region(Region *r, hipStream_t stream);
+// A call's hold on a region.  The constructor takes the scratch lock and a region for `stream`; the
+// destructor (also on an early error return) records the event that later hand-overs wait for and
+// drops the lock, so the kernels of one call reach the stream back to back and a region never
+// changes hands without that event.  slots() is the region's device address, nullptr when none can
+// be had.
+class ScratchLease {
+ public:
+  explicit ScratchLease(hipStream_t stream);
+  ~ScratchLease();
+  ScratchLease(const ScratchLease &) = delete;
+  ScratchLease &operator=(const ScratchLease &) = delete;
+  ew_cksum_t *slots() const { return slots_; }
+
+ private:
+  std::unique_lock<std::mutex> lock_;
+  hipStream_t stream_;
+  Region *region_ = nullptr;
+  ew_cksum_t *slots_ = nullptr;
+};
 
 // ---- pointer tables of the tile-driven kernels, passed by value ----------------------------------
 struct CopyTabs {

@@ -89,8 +89,10 @@ int launch_zero(void *p, uint64_t nbytes, hipStream_t stream) {
   return EW_OK;
 }
 
-std::mutex &scratch_mutex() { return g_scratch.mu; }
+namespace {
 
+// Caller holds g_scratch.mu.  Returns the region's device address (the region through *out), or
+// nullptr when none can be had.
 ew_cksum_t *acquire_region(hipStream_t stream, Region **out) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
@@ -127,6 +129,7 @@ ew_cksum_t *acquire_region(hipStream_t stream, Region **out) {
   return g_scratch.base[dev] + (uint64_t)pick * kRegionSlots;
 }
 
+// Caller holds g_scratch.mu; called after the last kernel of a call has been enqueued.
 void release_region(Region *r, hipStream_t stream) {
   r->last_use = ++g_scratch.clock;
   if (stream_is_capturing(stream)) {  // the graph's own ordering covers its replays on one stream
@@ -143,6 +146,17 @@ void release_region(Region *r, hipStream_t stream) {
     (void)hipGetLastError();
     (void)hipStreamSynchronize(stream);
   }
+}
+
+}  // namespace
+
+ScratchLease::ScratchLease(hipStream_t stream) : lock_(g_scratch.mu), stream_(stream) {
+  slots_ = acquire_region(stream, &region_);
+  if (!slots_) region_ = nullptr;
+}
+
+ScratchLease::~ScratchLease() {
+  if (region_) release_region(region_, stream_);
 }
 
 bool tables_usable(const ew_plan_t *plan) {

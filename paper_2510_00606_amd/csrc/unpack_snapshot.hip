@@ -197,9 +197,8 @@ extern "C" int ew_unpack_snapshot(const ew_plan_t *plan, const void *stage, cons
     st.nblk[k] = (uint32_t)nblk;
     if (st.nblk[k] > max_blk) max_blk = st.nblk[k];
   }
-  std::lock_guard<std::mutex> lock(ew::scratch_mutex());
-  ew::Region *region = nullptr;
-  ew_cksum_t *slots = ew::acquire_region(stream, &region);
+  ew::ScratchLease lease(stream);
+  ew_cksum_t *slots = lease.slots();
   if (!slots) return EW_ENOMEM;  // only for a capturing stream that owns no region
   hipLaunchKernelGGL(ew_zero_records_kernel, dim3((2 * max_blk + kThreads - 1) / kThreads, plan->new_dp),
                      dim3(kThreads), 0, stream, st);
@@ -210,6 +209,5 @@ extern "C" int ew_unpack_snapshot(const ew_plan_t *plan, const void *stage, cons
                                    : launch_pass<4>(tt, t0, n, tabs, st, slots, stream);
     if (prc != EW_OK) return prc;
   }
-  ew::release_region(region, stream);
   return EW_OK;
 }
