@@ -3,6 +3,7 @@
 // (ew_set_param, ew_get_param, ew_strerror, ew_version).
 #include "runtime.h"
 
+#include <atomic>
 #include <cstring>
 #include <string>
 
@@ -68,15 +69,17 @@ const char *last_hip_error() { return g_hip_error.c_str(); }
 Knobs &knobs() { return g_knobs; }
 
 int num_cus() {
-  static int cached[kMaxDevices] = {0};
+  static std::atomic<int> cached[kMaxDevices];  // zero-initialised; a race only repeats the query
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 256;
-  if (cached[dev] == 0) {
+  int n = cached[dev].load(std::memory_order_relaxed);
+  if (n == 0) {
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return 256;
-    cached[dev] = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    n = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    cached[dev].store(n, std::memory_order_relaxed);
   }
-  return cached[dev];
+  return n;
 }
 
 int launch_zero(void *p, uint64_t nbytes, hipStream_t stream) {
