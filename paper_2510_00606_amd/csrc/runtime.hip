@@ -82,6 +82,28 @@ int num_cus() {
   return n;
 }
 
+uint32_t occupancy_pad(int64_t wgs_per_cu) {
+  if (wgs_per_cu < 2 || wgs_per_cu > 7) return 0;  // 8 four-wave workgroups fill a CU's wave slots anyway
+  static std::atomic<int> cached[kMaxDevices];      // LDS bytes per CU
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 0;
+  int lds = cached[dev].load(std::memory_order_relaxed);
+  if (lds == 0) {
+    if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, dev) != hipSuccess || lds <= 0) {
+      (void)hipGetLastError();
+      return 0;
+    }
+    cached[dev].store(lds, std::memory_order_relaxed);
+  }
+  // n * (pad + margin) <= lds < (n + 1) * pad holds for n <= 7 with a 2 KiB margin (static LDS of the
+  // kernel plus the allocation granule) once lds >= 112 KiB; a workgroup may ask for at most 64 KiB
+  const int64_t kMargin = 2048, kMaxPerWorkgroup = 65536 - kMargin;
+  int64_t pad = (lds / wgs_per_cu - kMargin) & ~(int64_t)255;
+  if (pad > kMaxPerWorkgroup) pad = kMaxPerWorkgroup;
+  if (pad <= 0 || (wgs_per_cu + 1) * pad <= lds) return 0;  // would not cap at wgs_per_cu: leave it alone
+  return (uint32_t)pad;
+}
+
 int launch_zero(void *p, uint64_t nbytes, hipStream_t stream) {
   const uint64_t nwords = nbytes / 8;
   if (nwords == 0) return EW_OK;
@@ -208,6 +230,9 @@ int ew_set_param(const char *name, int64_t value) {
   } else if (!std::strcmp(name, "tile_elems")) {
     if (value < 0 || value > (1 << 24)) return EW_EINVAL;
     k.tile_elems = value;
+  } else if (!std::strcmp(name, "fused_wgs_per_cu")) {
+    if (value < 0 || value > 8 || value == 1) return EW_EINVAL;
+    k.fused_wgs_per_cu = value;
   } else if (!std::strcmp(name, "tile_align_bytes")) {
     if (value < 0 || value > 4096 || (value & (value - 1)) || (value && value < 16)) return EW_EINVAL;
     k.tile_align_bytes = value;
@@ -226,6 +251,7 @@ int64_t ew_get_param(const char *name) {
   if (!std::strcmp(name, "tile_elems")) return k.tile_elems;
   if (!std::strcmp(name, "tile_bytes")) return k.tile_bytes;
   if (!std::strcmp(name, "tile_align_bytes")) return k.tile_align_bytes;
+  if (!std::strcmp(name, "fused_wgs_per_cu")) return k.fused_wgs_per_cu;
   return -1;
 }
 

@@ -17,7 +17,7 @@ MIB = 1 << 20
 @pytest.fixture(autouse=True)
 def default_params():
     saved = {k: ew.ew_get_param(k) for k in ("tile_bytes", "tile_elems", "tile_align_bytes", "cksum_sub_bytes", "cksum_wgs_per_cu",
-                                              "cksum_mode")}
+                                              "cksum_mode", "fused_wgs_per_cu")}
     yield
     for k, v in saved.items():
         ew.ew_set_param(k, v)
@@ -277,6 +277,16 @@ def test_reshard_random_unit_boundaries(seed):
     ew.ew_set_param("tile_align_bytes", int(rng.choice([0, 16, 128, 256])))
     tile_elems = int(rng.choice([0, 0, 256, 1024, 3000]))
     reshard_case(old_dp, new_dp, mask, None, None, 2 + 2 * (seed & 1), rng, tile_elems, starts=starts)
+
+
+@pytest.mark.parametrize("wgs", [0, 2, 3, 5, 7, 8])
+def test_fused_unpack_with_occupancy_caps(wgs):
+    """The cap on resident workgroups changes the launch (dynamic LDS), never the result."""
+    ew.ew_set_param("fused_wgs_per_cu", wgs)
+    rng = np.random.default_rng(200 + wgs)
+    for es in (2, 4):
+        reshard_case(8, 7, 0xFF & ~(1 << 5), 3_000_000 + 8 * 37, 262144, es, rng)
+        reshard_case(3, 2, 0b111, 2_600_000, 99_992, es, rng)
 
 
 def test_null_buffers_are_rejected():

@@ -71,6 +71,13 @@ def test_error_codes():
         ew.ew_set_param("no_such_knob", 1)
     with pytest.raises(ew.EwError):
         ew.ew_set_param("cksum_sub_bytes", 3000)
+    assert ew.ew_get_param("fused_wgs_per_cu") == 6 and ew.ew_get_param("no_such_knob") == -1
+    for bad in (-1, 1, 9):
+        with pytest.raises(ew.EwError):
+            ew.ew_set_param("fused_wgs_per_cu", bad)
+    ew.ew_set_param("fused_wgs_per_cu", 4)
+    assert ew.ew_get_param("fused_wgs_per_cu") == 4
+    ew.ew_set_param("fused_wgs_per_cu", 6)
 
 
 def test_max_degree_and_wide_mask():
