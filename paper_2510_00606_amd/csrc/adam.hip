@@ -17,6 +17,7 @@
 #include <vector>
 
 #include "elaswave.h"
+#include "runtime.h"
 
 namespace {
 
@@ -190,14 +191,20 @@ int ew_adam_step(void *p_bf16, float *w, float *m, float *v, const void *grad, u
   if (grid > 0x7fffffffull) return EW_EINVAL;
   uint16_t *p = (uint16_t *)p_bf16;
   hipStream_t s = (hipStream_t)stream;
+  // Eight HBM streams per wave (four read, four written): with 12 one-wave workgroups resident per CU,
+  // three per SIMD, the step runs 7 % faster than with the 32 that fit (6.05 -> 6.50 TB/s measured in
+  // one process; 16: 6.34, 8: 6.03).
+  const uint32_t lds_pad = ew::occupancy_pad(ew::knobs().adam_wgs_per_cu, 0);
+  const dim3 g((uint32_t)grid), b(kThreads);
   if (grad_elem_size == 4) {
-    if (vec) hipLaunchKernelGGL((ew_adam_kernel<4, true>), dim3((uint32_t)grid), dim3(kThreads), 0, s, p, w, m, v, grad, n, *h);
-    else hipLaunchKernelGGL((ew_adam_kernel<4, false>), dim3((uint32_t)grid), dim3(kThreads), 0, s, p, w, m, v, grad, n, *h);
+    if (vec) hipLaunchKernelGGL((ew_adam_kernel<4, true>), g, b, lds_pad, s, p, w, m, v, grad, n, *h);
+    else hipLaunchKernelGGL((ew_adam_kernel<4, false>), g, b, lds_pad, s, p, w, m, v, grad, n, *h);
   } else {
-    if (vec) hipLaunchKernelGGL((ew_adam_kernel<2, true>), dim3((uint32_t)grid), dim3(kThreads), 0, s, p, w, m, v, grad, n, *h);
-    else hipLaunchKernelGGL((ew_adam_kernel<2, false>), dim3((uint32_t)grid), dim3(kThreads), 0, s, p, w, m, v, grad, n, *h);
+    if (vec) hipLaunchKernelGGL((ew_adam_kernel<2, true>), g, b, lds_pad, s, p, w, m, v, grad, n, *h);
+    else hipLaunchKernelGGL((ew_adam_kernel<2, false>), g, b, lds_pad, s, p, w, m, v, grad, n, *h);
   }
-  return hipGetLastError() == hipSuccess ? EW_OK : EW_EHIP;
+  EW_HIP(hipGetLastError());
+  return EW_OK;
 }
 
 int ew_adam_replay_host(void *p_bf16, float *w, float *m, float *v, const void *grad, uint32_t grad_elem_size,

@@ -225,11 +225,14 @@ int launch_cksum_streaming(const void *src, void *dst, uint64_t nbytes, ew_cksum
   }
   if (grid > 0x7fffffffull) grid = 0x7fffffffull;  // the kernel strides over what is left
   const bool aligned = ((((uintptr_t)src) | (COPY ? (uintptr_t)dst : 0)) & 15u) == 0;
+  // A read-only pass runs 2-3 % faster with four of these workgroups resident per CU than with the
+  // eight that fit (6.33 -> 6.50 TB/s measured in one process); the copying form wants all eight.
+  const uint32_t lds_pad = COPY ? 0u : ew::occupancy_pad(k.verify_wgs_per_cu, 4 * sizeof(uint64_t) * (kThreads / 64));
   if (aligned)
-    hipLaunchKernelGGL((ew_cksum_kernel<COPY, true>), dim3((uint32_t)grid), dim3(kThreads), 0, stream,
+    hipLaunchKernelGGL((ew_cksum_kernel<COPY, true>), dim3((uint32_t)grid), dim3(kThreads), lds_pad, stream,
                        (const char *)src, (char *)dst, nbytes, out, sub, accumulate);
   else
-    hipLaunchKernelGGL((ew_cksum_kernel<COPY, false>), dim3((uint32_t)grid), dim3(kThreads), 0, stream,
+    hipLaunchKernelGGL((ew_cksum_kernel<COPY, false>), dim3((uint32_t)grid), dim3(kThreads), lds_pad, stream,
                        (const char *)src, (char *)dst, nbytes, out, sub, accumulate);
   EW_HIP(hipGetLastError());
   return EW_OK;

@@ -31,16 +31,21 @@ struct Knobs {
   int64_t tile_bytes = 4096;        // default copy tile: 256 lanes x one 128-bit vector
   int64_t tile_elems = 0;           // > 0 overrides tile_bytes with a size in elements
   int64_t tile_align_bytes = 128;   // tile cuts fall on multiples of this in the destination (0: off)
-  int64_t fused_wgs_per_cu = 6;     // fused unpack + snapshot: workgroups resident per CU (2..7; 0 or 8: all that fit)
+  // Caps on the workgroups resident per CU (0 = all that fit) for the kernels that keep three or more
+  // HBM streams busy, or that read only: they run faster with fewer requests in flight.
+  int64_t fused_wgs_per_cu = 6;     // fused unpack + snapshot (256 lanes; 8 fit)
+  int64_t verify_wgs_per_cu = 4;    // read-only streaming checksum (256 lanes; 8 fit)
+  int64_t adam_wgs_per_cu = 12;     // optimizer step (one wave per workgroup; 32 fit)
 };
 Knobs &knobs();
 
 int num_cus();
 
-// Dynamic LDS bytes that, requested per 256-lane workgroup, leave room for exactly `wgs_per_cu`
-// workgroups on a CU of the current device (0 when no cap is wanted or none can be computed).
-// A kernel that keeps several HBM streams busy can run faster with fewer workgroups in flight.
-uint32_t occupancy_pad(int64_t wgs_per_cu);
+// Dynamic LDS bytes that, requested per workgroup of a kernel with `static_lds` bytes of its own,
+// leave room for exactly `wgs_per_cu` workgroups on a CU of the current device; 0 when no cap is
+// wanted (wgs_per_cu <= 0) or none can be guaranteed.  Occupancy is capped with LDS nobody uses
+// because nothing else limits it for these kernels (few registers, hardly any LDS).
+uint32_t occupancy_pad(int64_t wgs_per_cu, uint32_t static_lds);
 
 // Zero-fill by kernel (safe to record into a HIP graph); nbytes is a multiple of 8.
 int launch_zero(void *p, uint64_t nbytes, hipStream_t stream);

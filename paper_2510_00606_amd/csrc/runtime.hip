@@ -82,9 +82,9 @@ int num_cus() {
   return n;
 }
 
-uint32_t occupancy_pad(int64_t wgs_per_cu) {
-  if (wgs_per_cu < 2 || wgs_per_cu > 7) return 0;  // 8 four-wave workgroups fill a CU's wave slots anyway
-  static std::atomic<int> cached[kMaxDevices];      // LDS bytes per CU
+uint32_t occupancy_pad(int64_t wgs_per_cu, uint32_t static_lds) {
+  if (wgs_per_cu <= 0 || wgs_per_cu > 64) return 0;
+  static std::atomic<int> cached[kMaxDevices];  // LDS bytes per CU
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 0;
   int lds = cached[dev].load(std::memory_order_relaxed);
@@ -95,12 +95,13 @@ uint32_t occupancy_pad(int64_t wgs_per_cu) {
     }
     cached[dev].store(lds, std::memory_order_relaxed);
   }
-  // n * (pad + margin) <= lds < (n + 1) * pad holds for n <= 7 with a 2 KiB margin (static LDS of the
-  // kernel plus the allocation granule) once lds >= 112 KiB; a workgroup may ask for at most 64 KiB
-  const int64_t kMargin = 2048, kMaxPerWorkgroup = 65536 - kMargin;
-  int64_t pad = (lds / wgs_per_cu - kMargin) & ~(int64_t)255;
-  if (pad > kMaxPerWorkgroup) pad = kMaxPerWorkgroup;
-  if (pad <= 0 || (wgs_per_cu + 1) * pad <= lds) return 0;  // would not cap at wgs_per_cu: leave it alone
+  // largest pad (multiple of 256) with which wgs_per_cu workgroups still fit, allowing 512 bytes per
+  // workgroup for the allocation granule; a workgroup may ask for at most 64 KiB in all
+  const int64_t n = wgs_per_cu, kGranule = 512, kMaxPerWorkgroup = 65536;
+  int64_t pad = ((int64_t)lds / n) & ~(int64_t)255;
+  while (pad > 0 && n * (pad + static_lds + kGranule) > lds) pad -= 256;
+  if (pad + static_lds > kMaxPerWorkgroup) pad = (kMaxPerWorkgroup - static_lds) & ~(int64_t)255;
+  if (pad <= 0 || (n + 1) * pad <= lds) return 0;  // n + 1 might fit as well: no guarantee, no cap
   return (uint32_t)pad;
 }
 
@@ -231,8 +232,14 @@ int ew_set_param(const char *name, int64_t value) {
     if (value < 0 || value > (1 << 24)) return EW_EINVAL;
     k.tile_elems = value;
   } else if (!std::strcmp(name, "fused_wgs_per_cu")) {
-    if (value < 0 || value > 8 || value == 1) return EW_EINVAL;
+    if (value < 0 || value > 8) return EW_EINVAL;
     k.fused_wgs_per_cu = value;
+  } else if (!std::strcmp(name, "verify_wgs_per_cu")) {
+    if (value < 0 || value > 8) return EW_EINVAL;
+    k.verify_wgs_per_cu = value;
+  } else if (!std::strcmp(name, "adam_wgs_per_cu")) {
+    if (value < 0 || value > 32) return EW_EINVAL;
+    k.adam_wgs_per_cu = value;
   } else if (!std::strcmp(name, "tile_align_bytes")) {
     if (value < 0 || value > 4096 || (value & (value - 1)) || (value && value < 16)) return EW_EINVAL;
     k.tile_align_bytes = value;
@@ -252,6 +259,8 @@ int64_t ew_get_param(const char *name) {
   if (!std::strcmp(name, "tile_bytes")) return k.tile_bytes;
   if (!std::strcmp(name, "tile_align_bytes")) return k.tile_align_bytes;
   if (!std::strcmp(name, "fused_wgs_per_cu")) return k.fused_wgs_per_cu;
+  if (!std::strcmp(name, "verify_wgs_per_cu")) return k.verify_wgs_per_cu;
+  if (!std::strcmp(name, "adam_wgs_per_cu")) return k.adam_wgs_per_cu;
   return -1;
 }
 

@@ -162,7 +162,7 @@ int launch_pass(const ew::TileTable &tt, uint64_t t0, uint64_t n, const CopyTabs
   // 1-5 % faster (measured in one process, same buffers: 5.58 -> 5.84 TB/s in a slow placement of the
   // buffers, 6.04 -> 6.09 in a fast one; five per CU gains more in the slow case and loses in the
   // fast one, four loses in both).  The cap is set by asking for unused dynamic LDS.
-  const uint32_t lds_pad = ew::occupancy_pad(ew::knobs().fused_wgs_per_cu);
+  const uint32_t lds_pad = ew::occupancy_pad(ew::knobs().fused_wgs_per_cu, 8 * sizeof(uint64_t) * (kThreads / 64));
   hipLaunchKernelGGL(ew_unpack_snap_kernel<ES>, dim3((uint32_t)n), dim3(kThreads), lds_pad, stream, tt.dev, t0, tabs,
                      st, slots);
   EW_HIP(hipGetLastError());

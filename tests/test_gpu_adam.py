@@ -50,6 +50,17 @@ def test_device_step_is_bit_exact(n, shift, grad_bits):
     assert bool((pb[n:] == 0x5A5A).all()) and bool((wb[shift + n:] == 0).all()) and bool((wb[:shift] == 0).all())
 
 
+@pytest.mark.parametrize("wgs", [0, 1, 5, 12, 32])
+def test_device_step_with_occupancy_caps(wgs):
+    """The cap on resident workgroups changes the launch only, never the result."""
+    saved = ew.ew_get_param("adam_wgs_per_cu")
+    ew.ew_set_param("adam_wgs_per_cu", wgs)
+    try:
+        test_device_step_is_bit_exact(300_001, 0, 32)
+    finally:
+        ew.ew_set_param("adam_wgs_per_cu", saved)
+
+
 def test_device_step_special_values():
     w = np.array([0.0, -0.0, 1e-40, 1e38, -1e38, 1.0, 3e-39, 1.0], F)
     m = np.array([0.0, 1e-45, -1e-40, 1e30, 0.0, 1e-42, 0.0, 0.5], F)

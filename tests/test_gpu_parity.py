@@ -17,7 +17,7 @@ MIB = 1 << 20
 @pytest.fixture(autouse=True)
 def default_params():
     saved = {k: ew.ew_get_param(k) for k in ("tile_bytes", "tile_elems", "tile_align_bytes", "cksum_sub_bytes", "cksum_wgs_per_cu",
-                                              "cksum_mode", "fused_wgs_per_cu")}
+                                              "cksum_mode", "fused_wgs_per_cu", "verify_wgs_per_cu")}
     yield
     for k, v in saved.items():
         ew.ew_set_param(k, v)
@@ -123,6 +123,17 @@ def test_verify_clean_and_single_flip(mode):
         bad, diffs = verify_case(nbytes, [(o, bit)], rng)
         assert bad.tolist() == [o >> 20]
         assert int(diffs[0, 1]) == 1 << (8 * (o % 8) + bit)
+
+
+@pytest.mark.parametrize("wgs", [0, 1, 2, 4, 8])
+def test_verify_with_occupancy_caps(wgs):
+    """The cap on resident workgroups changes the launch only, never the result."""
+    ew.ew_set_param("verify_wgs_per_cu", wgs)
+    rng = np.random.default_rng(90 + wgs)
+    nbytes = 9 * MIB + 4096 * 3 + 11
+    o, bit = int(rng.integers(0, nbytes)), int(rng.integers(0, 8))
+    bad, diffs = verify_case(nbytes, [(o, bit)], rng)
+    assert bad.tolist() == [o >> 20] and int(diffs[0, 1]) == 1 << (8 * (o % 8) + bit)
 
 
 def test_verify_many_flips_ordered_and_capped():
