@@ -291,7 +291,7 @@ int ew_memcpy(const void *src, void *dst, uint64_t nbytes, void *stream);
  * "cksum_wgs_per_cu", "cksum_mode" (-1 = default: slot kernel + fold for ew_snapshot, atomic kernel
  * for ew_verify; 0 / 1 force the slot / atomic kernel for both), "fused_wgs_per_cu", "verify_wgs_per_cu",
  * "adam_wgs_per_cu" (workgroups resident per CU for the kernels of ew_unpack_snapshot, ew_verify and
- * ew_adam_step; 0 = all that fit; defaults 6, 4 and 12).
+ * ew_adam_step; 0 = all that fit; defaults 6, 4 and 11).
  * Returns EW_EINVAL for an unknown name or an out-of-range value. */
 int ew_set_param(const char *name, int64_t value);
 int64_t ew_get_param(const char *name);

@@ -191,9 +191,9 @@ int ew_adam_step(void *p_bf16, float *w, float *m, float *v, const void *grad, u
   if (grid > 0x7fffffffull) return EW_EINVAL;
   uint16_t *p = (uint16_t *)p_bf16;
   hipStream_t s = (hipStream_t)stream;
-  // Eight HBM streams per wave (four read, four written): with 12 one-wave workgroups resident per CU,
-  // three per SIMD, the step runs 7 % faster than with the 32 that fit (6.05 -> 6.50 TB/s measured in
-  // one process; 16: 6.34, 8: 6.03).
+  // Eight HBM streams per wave (four read, four written): with 11 one-wave workgroups resident per CU
+  // the step runs 7 % faster than with the 32 that fit (6.05 -> 6.52 TB/s measured in one process;
+  // 16: 6.34, 12: 6.48, 8: 6.03).
   const uint32_t lds_pad = ew::occupancy_pad(ew::knobs().adam_wgs_per_cu, 0);
   const dim3 g((uint32_t)grid), b(kThreads);
   if (grad_elem_size == 4) {

@@ -35,7 +35,7 @@ struct Knobs {
   // HBM streams busy, or that read only: they run faster with fewer requests in flight.
   int64_t fused_wgs_per_cu = 6;     // fused unpack + snapshot (256 lanes; 8 fit)
   int64_t verify_wgs_per_cu = 4;    // read-only streaming checksum (256 lanes; 8 fit)
-  int64_t adam_wgs_per_cu = 12;     // optimizer step (one wave per workgroup; 32 fit)
+  int64_t adam_wgs_per_cu = 11;     // optimizer step (one wave per workgroup; 32 fit)
 };
 Knobs &knobs();
 
