@@ -57,8 +57,9 @@ int launch_zero(void *p, uint64_t nbytes, hipStream_t stream);
 // (hipStreamWaitEvent, no host blocking) for the event recorded after the region's last use, so
 // two streams never touch a region at once.  A stream under graph capture can only use a region it
 // already owns (its warm-up run claims one); such a region stays with that stream for good, because
-// replays of the graph use it unseen.  One region (32 MiB) holds the slots of 2^21
-// workgroups, i.e. 8 GiB of input at 4 KiB per workgroup; longer inputs take several passes.
+// replays of the graph use it unseen.  One region (32 MiB) holds 2^21 slots: 2 GiB of
+// input for the snapshot kernel (one slot per wave and KiB), 2^21 tiles for the fused unpack (one slot
+// per tile); longer inputs take several passes.
 constexpr uint32_t kRegions = 4;
 constexpr uint64_t kRegionSlots = 1ull << 21;
 struct Region;

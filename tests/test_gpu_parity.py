@@ -409,7 +409,7 @@ def test_snapshot_from_several_host_threads():
 
 @pytest.mark.timeout(600)
 def test_snapshot_longer_than_one_scratch_pass():
-    """17 GiB + ragged tail: three passes over the 8 GiB scratch region."""
+    """17 GiB + ragged tail: nine passes over a scratch region, whose slots cover 2 GiB."""
     nbytes = 17 * (1 << 30) + 3 * MIB + 4096 + 5
     src = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
     g = torch.Generator(device=DEV)
@@ -428,7 +428,8 @@ def test_snapshot_longer_than_one_scratch_pass():
     assert torch.equal(src, dst)
     got = ck.cpu().numpy().view(np.uint64)
     # oracle on sampled blocks incl. both sides of every pass boundary and the ragged last block
-    blocks = sorted({0, 1, 8191, 8192, 8193, 16383, 16384, 16385, nb - 2, nb - 1} | set(np.random.default_rng(1).integers(0, nb, 24).tolist()))
+    blocks = sorted({0, 1, 2047, 2048, 2049, 4095, 4096, 8191, 8192, 8193, 16383, 16384, 16385, nb - 2, nb - 1}
+                    | set(np.random.default_rng(1).integers(0, nb, 24).tolist()))
     for b in blocks:
         host = src[b * MIB:min((b + 1) * MIB, nbytes)].cpu().numpy()
         assert np.array_equal(got[b], checksum.block_checksums(host)[0]), f"block {b}"
