@@ -280,10 +280,10 @@ int ew_grad_ship(const void *grad_dev, void *peer_dev, void *host_buf, uint64_t 
 int ew_checksum_host(const void *buf, uint64_t nbytes, ew_cksum_t *cksums, uint32_t n_threads);
 
 /* Plain device copy dst[0..nbytes) = src[0..nbytes) with the access pattern of the copy tiles
- * (128-bit vectors, 4 KiB per workgroup) and nothing else: the yardstick that benchmarks quote
+ * (one 128-bit vector per lane) and nothing else: the yardstick that benchmarks quote
  * the other kernels against and that profiler byte counters are calibrated with.  Not part of
  * the paper's method.  src, dst: device, 16-byte aligned, non-overlapping; nbytes a multiple of
- * 16 and at most (2^31-1) * 4 KiB, else EW_EINVAL. */
+ * 16 and at most (2^31-1) KiB, else EW_EINVAL. */
 int ew_memcpy(const void *src, void *dst, uint64_t nbytes, void *stream);
 
 /* Launch-shape knobs for benchmarking sweeps (process-wide, not thread-safe; defaults are the
