@@ -289,9 +289,10 @@ int ew_memcpy(const void *src, void *dst, uint64_t nbytes, void *stream);
 /* Launch-shape knobs for benchmarking sweeps (process-wide, not thread-safe; defaults are the
  * tuned ones).  Names: "tile_bytes", "tile_elems", "tile_align_bytes", "cksum_sub_bytes",
  * "cksum_wgs_per_cu", "cksum_mode" (-1 = default: slot kernel + fold for ew_snapshot, atomic kernel
- * for ew_verify; 0 / 1 force the slot / atomic kernel for both), "fused_wgs_per_cu", "verify_wgs_per_cu",
- * "adam_wgs_per_cu" (workgroups resident per CU for the kernels of ew_unpack_snapshot, ew_verify and
- * ew_adam_step; 0 = all that fit; defaults 6, 4 and 11).
+ * for ew_verify; 0 / 1 force the slot / atomic kernel for both), "snapshot_wave_min_bytes"
+ * (ew_snapshot uses one-wave workgroups from this size on, 256-lane ones below; default 128 MiB),
+ * "fused_wgs_per_cu", "verify_wgs_per_cu", "adam_wgs_per_cu" (workgroups resident per CU for the
+ * kernels of ew_unpack_snapshot, ew_verify and ew_adam_step; 0 = all that fit; defaults 6, 4, 11).
  * Returns EW_EINVAL for an unknown name or an out-of-range value. */
 int ew_set_param(const char *name, int64_t value);
 int64_t ew_get_param(const char *name);

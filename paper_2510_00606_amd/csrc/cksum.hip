@@ -99,17 +99,19 @@ __global__ __launch_bounds__(kThreads) void ew_cksum_kernel(const char *__restri
 
 // Fast form of the copy for 16-byte aligned buffers.  Measured on MI355X, a copy runs fastest as a
 // flood of small workgroups in which every lane moves ONE 128-bit vector, and 64-bit atomics from
-// many workgroups onto one checksum record serialise badly.  So: a workgroup is a single wave, it
-// folds its 1 KiB into one (sum, xor) pair with DPP moves and lane 63 writes the pair to the wave's
-// own 16-byte slot of a scratch region: no LDS, no barrier, no atomics, no zero-fill.
-// ew_fold_kernel then folds the 1024 slots of every 1 MiB block into the block's record.  (With
-// 256-lane workgroups, the four waves meeting in LDS and one slot per 4 KiB, the same pass is
-// 2 % slower: 6.32 against 6.45 TB/s in one process.)
-constexpr uint32_t kSlotBytes = 1024;  // one wave x one 128-bit vector per lane
-template <bool COPY>
-__global__ __launch_bounds__(64) void ew_cksum_slots_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst,
-                                                            uint64_t nbytes, ew_cksum_t *__restrict__ slots) {
-  const uint64_t i = (uint64_t)blockIdx.x * 64 + threadIdx.x;
+// many workgroups onto one checksum record serialise badly.  So: a workgroup of WAVES waves folds its
+// WAVES KiB into one (sum, xor) pair and writes it to its own 16-byte slot of a scratch region (no
+// atomics, no zero-fill), and ew_fold_kernel then folds the slots of every 1 MiB block into the
+// block's record.  WAVES = 1 (the wave folds with DPP moves, lane 63 writes the slot: no LDS, no
+// barrier) is the faster shape for large buffers (6.45 against 6.32 TB/s on 0.875 GB); WAVES = 4
+// (the four waves meet in LDS) has a quarter of the workgroups and slots and is a little quicker
+// below about 100 MiB, where launch and drain times weigh more (9.2 against 9.8 us for 1 MiB).
+template <bool COPY, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void ew_cksum_slots_kernel(const u32x4 *__restrict__ src,
+                                                                    u32x4 *__restrict__ dst, uint64_t nbytes,
+                                                                    ew_cksum_t *__restrict__ slots) {
+  static_assert(WAVES == 1 || 64 * WAVES == kThreads, "block_fold is written for kThreads lanes");
+  const uint64_t i = (uint64_t)blockIdx.x * (64 * WAVES) + threadIdx.x;
   const uint64_t nvec = nbytes >> 4;
   uint64_t sum = 0, xr = 0;
   if (i < nvec) {
@@ -129,24 +131,29 @@ __global__ __launch_bounds__(64) void ew_cksum_slots_kernel(const u32x4 *__restr
     sum = w[0] + w[1];
     xr = w[0] ^ w[1];
   }
-  ew::wave_fold(sum, xr);
-  if (threadIdx.x == ew::kWaveFoldLane) {
-    ew_cksum_t r;
-    r.sum = sum;
-    r.xr = xr;
-    slots[blockIdx.x] = r;
+  if (WAVES == 1) {
+    ew::wave_fold(sum, xr);
+    if (threadIdx.x != ew::kWaveFoldLane) return;
+  } else {
+    __shared__ uint64_t lds_sum[WAVES];
+    __shared__ uint64_t lds_xor[WAVES];
+    block_fold(sum, xr, lds_sum, lds_xor);
+    if (threadIdx.x != 0) return;
   }
+  ew_cksum_t r;
+  r.sum = sum;
+  r.xr = xr;
+  slots[blockIdx.x] = r;
 }
 
-// One workgroup per checksum block: folds the block's slots (1024 for a full block) into out[b].
+// One workgroup per checksum block: folds the block's slots (per_block for a full block) into out[b].
 __global__ __launch_bounds__(kThreads) void ew_fold_kernel(const ew_cksum_t *__restrict__ slots, uint64_t nslots,
-                                                           ew_cksum_t *__restrict__ out) {
+                                                           uint32_t per_block, ew_cksum_t *__restrict__ out) {
   __shared__ uint64_t lds_sum[kThreads / 64];
   __shared__ uint64_t lds_xor[kThreads / 64];
-  constexpr uint32_t kSlotsPerBlock = EW_CKSUM_BLOCK / kSlotBytes;
   uint64_t sum = 0, xr = 0;
-  for (uint32_t t = threadIdx.x; t < kSlotsPerBlock; t += kThreads) {
-    const uint64_t sidx = (uint64_t)blockIdx.x * kSlotsPerBlock + t;
+  for (uint32_t t = threadIdx.x; t < per_block; t += kThreads) {
+    const uint64_t sidx = (uint64_t)blockIdx.x * per_block + t;
     if (sidx < nslots) {
       const ew_cksum_t r = slots[sidx];
       sum += r.sum;
@@ -248,19 +255,25 @@ int launch_cksum(const void *src, void *dst, uint64_t nbytes, ew_cksum_t *out, h
   ew::ScratchLease lease(stream);
   ew_cksum_t *slots = lease.slots();
   if (!slots) return launch_cksum_streaming<COPY>(src, dst, nbytes, out, stream);  // needs no scratch
-  constexpr uint64_t kPassBytes = ew::kRegionSlots * kSlotBytes;  // what one region's slots cover: 2 GiB
-  for (uint64_t off = 0; off < nbytes; off += kPassBytes) {
-    const uint64_t n = nbytes - off < kPassBytes ? nbytes - off : kPassBytes;
-    // one wave (and slot) per KiB; a partial trailing vector belongs to lane n/16, which the last
-    // wave always contains because ceil(n/1024)*64 > n/16 whenever 16 does not divide n
-    const uint64_t grid = (n + kSlotBytes - 1) / kSlotBytes;
+  // one slot per KiB (one-wave workgroups) from snapshot_wave_min_bytes on, one per 4 KiB below
+  const bool one_wave = nbytes >= (uint64_t)ew::knobs().snapshot_wave_min_bytes;
+  const uint64_t slot_bytes = one_wave ? 1024 : 4096;
+  const uint64_t pass_bytes = ew::kRegionSlots * slot_bytes;  // what one region's slots cover
+  for (uint64_t off = 0; off < nbytes; off += pass_bytes) {
+    const uint64_t n = nbytes - off < pass_bytes ? nbytes - off : pass_bytes;
+    // a partial trailing vector belongs to lane n/16, which the last workgroup always contains because
+    // ceil(n/slot_bytes) * slot_bytes/16 > n/16 whenever 16 does not divide n
+    const uint64_t grid = (n + slot_bytes - 1) / slot_bytes;
     const uint64_t nblk = (n + EW_CKSUM_BLOCK - 1) / EW_CKSUM_BLOCK;
-    hipLaunchKernelGGL((ew_cksum_slots_kernel<COPY>), dim3((uint32_t)grid), dim3(64), 0, stream,
-                       (const u32x4 *)((const char *)src + off), (u32x4 *)(COPY ? (char *)dst + off : nullptr), n,
-                       slots);
+    const u32x4 *s = (const u32x4 *)((const char *)src + off);
+    u32x4 *d = (u32x4 *)(COPY ? (char *)dst + off : nullptr);
+    if (one_wave)
+      hipLaunchKernelGGL((ew_cksum_slots_kernel<COPY, 1>), dim3((uint32_t)grid), dim3(64), 0, stream, s, d, n, slots);
+    else
+      hipLaunchKernelGGL((ew_cksum_slots_kernel<COPY, 4>), dim3((uint32_t)grid), dim3(256), 0, stream, s, d, n, slots);
     EW_HIP(hipGetLastError());
     hipLaunchKernelGGL(ew_fold_kernel, dim3((uint32_t)nblk), dim3(kThreads), 0, stream, slots, grid,
-                       out + off / EW_CKSUM_BLOCK);
+                       (uint32_t)(EW_CKSUM_BLOCK / slot_bytes), out + off / EW_CKSUM_BLOCK);
     EW_HIP(hipGetLastError());
   }
   return EW_OK;

@@ -28,6 +28,7 @@ struct Knobs {
                                     // else a persistent grid of this many workgroups per CU
   int64_t cksum_mode = -1;          // -1 = slot kernel + fold for snapshot, streaming kernel for verify;
                                     // 0 / 1 force the slot / streaming kernel for both
+  int64_t snapshot_wave_min_bytes = 128 << 20;  // snapshot: one-wave workgroups from this size on, 256 lanes below
   int64_t tile_bytes = 4096;        // default copy tile: 256 lanes x one 128-bit vector
   int64_t tile_elems = 0;           // > 0 overrides tile_bytes with a size in elements
   int64_t tile_align_bytes = 128;   // tile cuts fall on multiples of this in the destination (0: off)

@@ -225,6 +225,9 @@ int ew_set_param(const char *name, int64_t value) {
   } else if (!std::strcmp(name, "cksum_wgs_per_cu")) {
     if (value < 0 || value > 64) return EW_EINVAL;
     k.cksum_wgs_per_cu = value;
+  } else if (!std::strcmp(name, "snapshot_wave_min_bytes")) {
+    if (value < 0) return EW_EINVAL;
+    k.snapshot_wave_min_bytes = value;
   } else if (!std::strcmp(name, "cksum_mode")) {
     if (value < -1 || value > 1) return EW_EINVAL;
     k.cksum_mode = value;
@@ -258,6 +261,7 @@ int64_t ew_get_param(const char *name) {
   if (!std::strcmp(name, "cksum_sub_bytes")) return k.cksum_sub_bytes;
   if (!std::strcmp(name, "cksum_wgs_per_cu")) return k.cksum_wgs_per_cu;
   if (!std::strcmp(name, "cksum_mode")) return k.cksum_mode;
+  if (!std::strcmp(name, "snapshot_wave_min_bytes")) return k.snapshot_wave_min_bytes;
   if (!std::strcmp(name, "tile_elems")) return k.tile_elems;
   if (!std::strcmp(name, "tile_bytes")) return k.tile_bytes;
   if (!std::strcmp(name, "tile_align_bytes")) return k.tile_align_bytes;

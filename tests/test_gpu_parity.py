@@ -17,7 +17,7 @@ MIB = 1 << 20
 @pytest.fixture(autouse=True)
 def default_params():
     saved = {k: ew.ew_get_param(k) for k in ("tile_bytes", "tile_elems", "tile_align_bytes", "cksum_sub_bytes", "cksum_wgs_per_cu",
-                                              "cksum_mode", "fused_wgs_per_cu", "verify_wgs_per_cu")}
+                                              "cksum_mode", "fused_wgs_per_cu", "verify_wgs_per_cu", "snapshot_wave_min_bytes")}
     yield
     for k, v in saved.items():
         ew.ew_set_param(k, v)
@@ -50,6 +50,13 @@ SIZES = [0, 1, 7, 8, 9, 15, 16, 17, 255, 4096, 4096 * 3 + 5, 65536, 65536 + 16, 
 @pytest.mark.parametrize("nbytes", SIZES)
 def test_snapshot_matches_oracle(nbytes):
     snapshot_case(nbytes, np.random.default_rng(nbytes))
+
+
+@pytest.mark.parametrize("nbytes", SIZES)
+def test_snapshot_one_wave_shape_on_small_buffers(nbytes):
+    """The shape meant for large buffers, forced on every size."""
+    ew.ew_set_param("snapshot_wave_min_bytes", 0)
+    snapshot_case(nbytes, np.random.default_rng(nbytes + 1))
 
 
 @pytest.mark.parametrize("sub,wgs", [(4096, 0), (16384, 2), (65536, 0), (262144, 1), (MIB, 0), (MIB, 3)])
