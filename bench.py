@@ -75,11 +75,11 @@ def read_traffic(kernel_key):
 
 def merge_paths(parts):
     """Sums the per-array measurements of one path."""
-    out = {"ms_per_step": 0.0, "plan_ms": 0.0, "phase_ms": {}, "bytes_phase": {}, "launches": {}}
+    out = {"ms_per_step": 0.0, "plan_ms": 0.0, "phase_ms": {}, "phase_median_ms": {}, "bytes_phase": {}, "launches": {}}
     for p in parts:
         out["ms_per_step"] += p["ms_per_step"]
         out["plan_ms"] += p["plan_ms"]
-        for key in ("phase_ms", "bytes_phase", "launches"):
+        for key in ("phase_ms", "phase_median_ms", "bytes_phase", "launches"):
             for ph, v in p[key].items():
                 out[key][ph] = out[key].get(ph, 0) + v
     return out
@@ -92,7 +92,8 @@ def summarise(path, workload_name):
     for ph in phase_ms:
         if phase_ms[ph] > 0:
             gbs = bytes_phase[ph] / phase_ms[ph] / 1e6
-            kernels[ph] = {"ms": round(phase_ms[ph], 4), "launches": launches[ph], "GB": round(bytes_phase[ph] / 1e9, 4),
+            kernels[ph] = {"ms": round(phase_ms[ph], 4), "ms_median": round(path["phase_median_ms"][ph], 4),
+                           "launches": launches[ph], "GB": round(bytes_phase[ph] / 1e9, 4),
                            "GB/s": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4)}
     # dominant kernel: the one whose launches take the most time in a step
     groups = {}
@@ -222,8 +223,10 @@ def measure(args, ew, synth, torch, w, starts, A, keep_state):
             p.close()
         assert int(n_bad.item()) == 0, "verification of an intact snapshot reported bad blocks"
         phase_ms = {ph: sum(ev[i].elapsed_time(ev[i + 1]) for _, ev in records) / steps for i, ph in enumerate(phases)}
+        phase_median = {ph: sorted(ev[i].elapsed_time(ev[i + 1]) for _, ev in records)[steps // 2]
+                        for i, ph in enumerate(phases)}
         return {"ms_per_step": elapsed / steps * 1e3, "plan_ms": sum(r[0] for r in records) / steps * 1e3,
-                "phase_ms": phase_ms, "bytes_phase": bytes_phase, "launches": launches}
+                "phase_ms": phase_ms, "phase_median_ms": phase_median, "bytes_phase": bytes_phase, "launches": launches}
 
     # ---------------- the timed region (inside run_path): exactly K steps of the headline path
     head = run_path(args.unfused, args.steps, args.warmup)
