@@ -265,6 +265,26 @@ def measure(args, ew, synth, torch, w, starts, A, keep_state):
         rp.close()
     reshard_only_ms = sorted(reshard_runs)[len(reshard_runs) // 2]
 
+    # the same without the arena (holders and destinations in one address space, as on this one GPU):
+    # plan + upload + ew_reshard of the four arrays, and the variant that also takes the new snapshot
+    direct_runs, direct_snap_runs = [], []
+    for _ in range(7):
+        for runs, with_snapshot in ((direct_runs, False), (direct_snap_runs, True)):
+            torch.cuda.synchronize()
+            r0 = time.perf_counter()
+            rp = ew.ew_plan_bounds(w.old_dp, w.new_dp, w.alive_mask, starts)
+            ew.ew_plan_upload(rp, 0, st)
+            for a in A:
+                if with_snapshot:
+                    ew.ew_reshard_snapshot(rp, old_after[a], snap_used[a], new[a], nsnap[a], nsums[a], es[a], st)
+                else:
+                    ew.ew_reshard(rp, old_after[a], snap_used[a], new[a], es[a], st)
+            torch.cuda.synchronize()
+            runs.append((time.perf_counter() - r0) * 1e3)
+            rp.close()
+    direct_ms = sorted(direct_runs)[len(direct_runs) // 2]
+    direct_snap_ms = sorted(direct_snap_runs)[len(direct_snap_runs) // 2]
+
     tiny_latency = None
     if w.name == "tiny":
         # cache-resident and launch bound: read these as latencies, not as fractions of HBM peak.  The
@@ -302,7 +322,8 @@ def measure(args, ew, synth, torch, w, starts, A, keep_state):
             lat[name + "_us"] = round((time.perf_counter() - t0) / 50 * 1e6, 1)
         tiny_latency = lat
         gplan.close()
-    return {"head": head, "other": other, "copy_gbs": copy_gbs, "reshard_only_ms": reshard_only_ms, "n_remote": n_remote,
+    return {"head": head, "other": other, "copy_gbs": copy_gbs, "reshard_only_ms": reshard_only_ms, "direct_ms": direct_ms,
+            "direct_snap_ms": direct_snap_ms, "n_remote": n_remote,
             "old_len": old_len, "keep": (old, alive) if keep_state else None, "tiny_latency": tiny_latency}
 
 
@@ -341,6 +362,8 @@ def main():
     other = None if parts[0]["other"] is None else summarise(merge_paths([p["other"] for p in parts]), w.name)
     copy_gbs = parts[-1]["copy_gbs"]
     reshard_only_ms = sum(p["reshard_only_ms"] for p in parts)
+    direct_ms = sum(p["direct_ms"] for p in parts)
+    direct_snap_ms = sum(p["direct_snap_ms"] for p in parts)
     n_remote = parts[0]["n_remote"]
     old_len = parts[0]["old_len"]
     old, alive = parts[0]["keep"] if parts[0]["keep"] else (None, None)
@@ -360,6 +383,12 @@ def main():
         "path": names[args.unfused],
         "reshard_one_stage_ms": round(reshard_only_ms, 3),
         "reshard_useful_GBps": round(14 * numel / reshard_only_ms / 1e6, 1),
+        "reshard_without_arena": {
+            "note": "ew_reshard: every segment pulled straight from its holder's buffer, for ranks in one address "
+                    "space (outside `value`, which keeps the pack -> arena -> unpack path)",
+            "reshard_ms": round(direct_ms, 3), "GBps": round(28 * numel / direct_ms / 1e6, 1),
+            "reshard_plus_new_snapshot_ms": round(direct_snap_ms, 3),
+            "reshard_plus_new_snapshot_GBps": round(42 * numel / direct_snap_ms / 1e6, 1)},
         "plan_ms": round(head["plan_ms"], 3),
         "step_GB": round(head["step_GB"], 3),
         "kernels": head["kernels"],

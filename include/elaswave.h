@@ -163,7 +163,7 @@ typedef struct {
   uint16_t src_buf;
   uint16_t dst_buf;
 } ew_tile_t;
-/* Writes tiles [first, first+count) of the table for `which` (0 pack, 1 unpack), cut at
+/* Writes tiles [first, first+count) of the table for `which` (0 pack, 1 unpack, 2 direct), cut at
  * tile_elems elements with cut points on multiples of align_elems in the destination (0: no
  * alignment), into out[] (host) and the table's tile count into *total (may be NULL). */
 int ew_plan_tiles(const ew_plan_t *plan, int which, uint32_t tile_elems, uint32_t align_elems, uint64_t first,
@@ -209,6 +209,20 @@ int ew_unpack(const ew_plan_t *plan, const void *stage, const void *const *old_s
 int ew_unpack_snapshot(const ew_plan_t *plan, const void *stage, const void *const *old_shards,
                        const void *const *snapshots, void *const *new_shards, void *const *new_snapshots,
                        ew_cksum_t *const *new_cksums, uint32_t elem_size, void *stream);
+
+/* ---- Live Remap steps 3 and 4 without the arena ------------------------------------------------
+ * Where holders and destinations share one address space -- all ranks in one GPU's memory as here,
+ * or load/store-mapped peers -- a destination can pull every segment straight from the holder's
+ * live shard or snapshot (Fig. 7a: "pulls from DP 1's device", "from DP 1's host snapshot") and
+ * the pair messages need not be materialised: new_shards as after ew_pack + ew_unpack, 28 B per
+ * element of traffic less for every remote element.  ew_reshard_snapshot adds the snapshot copies
+ * and checksums of the new shards exactly as ew_unpack_snapshot does.  Arguments, errors and
+ * scratch use as for ew_unpack / ew_unpack_snapshot, minus `stage`. */
+int ew_reshard(const ew_plan_t *plan, const void *const *old_shards, const void *const *snapshots,
+               void *const *new_shards, uint32_t elem_size, void *stream);
+int ew_reshard_snapshot(const ew_plan_t *plan, const void *const *old_shards, const void *const *snapshots,
+                        void *const *new_shards, void *const *new_snapshots, ew_cksum_t *const *new_cksums,
+                        uint32_t elem_size, void *stream);
 
 /* ---- Per-step snapshot (Sec. 5.1) with block checksums ------------------------------------
  * dst[0..nbytes) = src[0..nbytes); cksums[b] = (wrapping u64 sum, XOR) of the little-endian

@@ -67,6 +67,9 @@ _SIGNATURES = {
     "ew_unpack": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p]),
     "ew_unpack_snapshot": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_uint32, C.c_void_p]),
+    "ew_reshard": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p]),
+    "ew_reshard_snapshot": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32,
+                                      C.c_void_p]),
     "ew_snapshot": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]),
     "ew_verify": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                             C.c_uint64, C.c_void_p]),
@@ -318,6 +321,36 @@ def ew_unpack_snapshot(plan: Plan, stage, old_shards, snapshots, new_shards, new
                                     _ptr_array(snapshots, plan.old_dp), _ptr_array(new_shards, D),
                                     _ptr_array(new_snapshots, D), _ptr_array(new_cksums, D), elem_size,
                                     _stream(stream)), "ew_unpack_snapshot")
+
+
+def _check_new(plan, new_shards, new_snapshots, new_cksums, elem_size):
+    for k in range(plan.new_dp):
+        need = plan.new_shard_len(k) * elem_size
+        for name, bufs, want in (("new shard", new_shards, need), ("new snapshot", new_snapshots, need),
+                                 ("new checksum array", new_cksums, 16 * num_blocks(need))):
+            if bufs is None:
+                continue
+            n = _nbytes(bufs[k]) if bufs[k] is not None else None
+            if n is not None and n < want:
+                raise ValueError(f"{name} {k} holds {n} bytes, plan needs {want}")
+
+
+def ew_reshard(plan: Plan, old_shards, snapshots, new_shards, elem_size: int, stream=None):
+    _check_sources(plan, old_shards, snapshots, elem_size)
+    _check_new(plan, new_shards, None, None, elem_size)
+    _check(lib().ew_reshard(plan.handle, _ptr_array(old_shards, plan.old_dp), _ptr_array(snapshots, plan.old_dp),
+                            _ptr_array(new_shards, plan.new_dp), elem_size, _stream(stream)), "ew_reshard")
+
+
+def ew_reshard_snapshot(plan: Plan, old_shards, snapshots, new_shards, new_snapshots, new_cksums, elem_size: int,
+                        stream=None):
+    _check_sources(plan, old_shards, snapshots, elem_size)
+    _check_new(plan, new_shards, new_snapshots, new_cksums, elem_size)
+    D = plan.new_dp
+    _check(lib().ew_reshard_snapshot(plan.handle, _ptr_array(old_shards, plan.old_dp),
+                                     _ptr_array(snapshots, plan.old_dp), _ptr_array(new_shards, D),
+                                     _ptr_array(new_snapshots, D), _ptr_array(new_cksums, D), elem_size,
+                                     _stream(stream)), "ew_reshard_snapshot")
 
 
 def num_blocks(nbytes: int) -> int:

@@ -90,7 +90,7 @@ void release_tables(ew_plan_t *plan) {
   plan->dev_buf = plan->host_buf = nullptr;
   plan->uploaded = false;
   plan->device = -1;
-  for (int w = 0; w < 2; ++w)
+  for (int w = 0; w < ew::kNumTables; ++w)
     for (int e = 0; e < 2; ++e) plan->tables[w][e] = ew::TileTable();
 }
 
@@ -119,7 +119,7 @@ void ew_plan_free(ew_plan_t *plan) {
 }
 
 uint64_t ew_plan_num_tiles(const ew_plan_t *plan, int which, uint32_t elem_size) {
-  if (!plan || (which != 0 && which != 1) || (elem_size != 2 && elem_size != 4)) return 0;
+  if (!plan || which < 0 || which >= ew::kNumTables || (elem_size != 2 && elem_size != 4)) return 0;
   const int e = elem_size == 4 ? 1 : 0;
   if (plan->uploaded) return plan->tables[which][e].ntiles;
   const ew::Knobs &k = ew::knobs();
@@ -144,7 +144,7 @@ int ew_plan_upload(ew_plan_t *plan, uint32_t tile_elems, void *stream) {
     for (int e = 0; e < 2; ++e) {
       const uint32_t es = e ? 4u : 2u;
       plan->tile_elems[e] = tile_elems ? tile_elems : (uint32_t)(k.tile_bytes / es);
-      for (int w = 0; w < 2; ++w) {
+      for (int w = 0; w < ew::kNumTables; ++w) {
         ew::TileTable &tt = plan->tables[w][e];
         ew::build_tile_table(*plan, w, plan->tile_elems[e], (uint32_t)(k.tile_align_bytes / es), tt);
         if (tt.ntiles > 0x7fffffffull) {  // tile ids are workgroup ids
@@ -173,7 +173,7 @@ int ew_plan_upload(ew_plan_t *plan, uint32_t tile_elems, void *stream) {
     }
     size_t off = 0;
     char *h = (char *)plan->host_buf, *d = (char *)plan->dev_buf;
-    for (int w = 0; w < 2; ++w)
+    for (int w = 0; w < ew::kNumTables; ++w)
       for (int e = 0; e < 2; ++e) {  // templates (48 B records) first keeps everything 16-byte aligned
         ew::TileTable &tt = plan->tables[w][e];
         const size_t tb = tt.templ.size() * sizeof(TileT), rb = tt.runs.size() * sizeof(RunT);
@@ -226,6 +226,22 @@ int ew_unpack(const ew_plan_t *plan, const void *stage, const void *const *old_s
   const int rc = ew::fill_tabs(plan, old_shards, snapshots, tabs);
   if (rc != EW_OK) return rc;
   tabs.src[ew::kSrcStage] = (const char *)stage;
+  for (uint32_t k = 0; k < plan->new_dp; ++k) {
+    if (plan->new_len[k] > 0 && !new_shards[k]) return EW_EINVAL;
+    tabs.dst[k] = (char *)new_shards[k];
+  }
+  return launch_segcopy(tt, tabs, elem_size, (hipStream_t)stream);
+}
+
+int ew_reshard(const ew_plan_t *plan, const void *const *old_shards, const void *const *snapshots,
+               void *const *new_shards, uint32_t elem_size, void *stream) {
+  if (!ew::tables_usable(plan) || (elem_size != 2 && elem_size != 4)) return EW_EINVAL;
+  const ew::TileTable &tt = plan->tables[2][elem_size == 4 ? 1 : 0];
+  if (tt.ntiles == 0) return EW_OK;
+  if (!new_shards) return EW_EINVAL;
+  CopyTabs tabs;
+  const int rc = ew::fill_tabs(plan, old_shards, snapshots, tabs);
+  if (rc != EW_OK) return rc;
   for (uint32_t k = 0; k < plan->new_dp; ++k) {
     if (plan->new_len[k] > 0 && !new_shards[k]) return EW_EINVAL;
     tabs.dst[k] = (char *)new_shards[k];

@@ -288,7 +288,7 @@ void build_tile_table(const ew_plan_t &plan, int which, uint32_t tile_elems, uin
         pc.dst = s.stage_off;
         pc.src_stride = s.src_stride;
         pc.dst_stride = s.stage_stride;
-      } else if (local) {  // source buffer -> new shard
+      } else if (local || which == 2) {  // source buffer -> new shard
         pc.src_buf = data_buf;
         pc.dst_buf = s.dst_rank;
         pc.src = s.src_off;
@@ -464,7 +464,7 @@ int ew_plan_migrate(uint32_t assignment, uint32_t dp, uint64_t n_src_units, cons
 
 int ew_plan_tiles(const ew_plan_t *p, int which, uint32_t tile_elems, uint32_t align_elems, uint64_t first,
                   uint64_t count, ew_tile_t *out, uint64_t *total) {
-  if (!p || (which != 0 && which != 1) || tile_elems == 0 || tile_elems > (1u << 24)) return EW_EINVAL;
+  if (!p || which < 0 || which >= ew::kNumTables || tile_elems == 0 || tile_elems > (1u << 24)) return EW_EINVAL;
   if (count > 0 && !out) return EW_EINVAL;
   try {
     ew::TileTable tt;

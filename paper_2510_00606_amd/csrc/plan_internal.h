@@ -60,6 +60,7 @@ constexpr uint32_t kSrcStage = 2 * EW_MAX_DP;
 constexpr uint32_t kNumSrc = 2 * EW_MAX_DP + 1;
 constexpr uint32_t kDstStage = EW_MAX_DP;
 constexpr uint32_t kNumDst = EW_MAX_DP + 1;
+constexpr int kNumTables = 3;  // pack, unpack, direct
 
 // Tile id -> (buffers, offsets, length).  The one decoder, used by the copy kernel (where every
 // operand is wave-uniform and lives in scalar registers) and by the host-side ew_plan_tiles.
@@ -136,14 +137,15 @@ struct ew_plan_s {
   bool uploaded = false;
   int device = -1;  // device that holds dev_buf; pack / unpack refuse to launch on another
   uint32_t tile_elems[2] = {0, 0};              // [0]: 2-byte elements, [1]: 4-byte elements
-  ew::TileTable tables[2][2];                   // [which: 0 pack, 1 unpack][elem size index]
+  ew::TileTable tables[3][2];                   // [which: 0 pack, 1 unpack, 2 direct][elem size index]
   void *host_buf = nullptr;                     // pinned staging copy, kept until the plan is freed
   void *dev_buf = nullptr;
 };
 
 namespace ew {
-// Cuts the plan's run segments into tile templates.  which = 0: non-LOCAL segments, source ->
-// arena.  which = 1: every segment, arena or local source -> new shard.
+// Cuts the plan's run segments into tile templates.  which = 0 (pack): non-LOCAL segments, source ->
+// arena.  which = 1 (unpack): every segment, arena or local source -> new shard.  which = 2 (direct):
+// every segment, source -> new shard, no arena.
 // Cuts inside a segment fall on multiples of align_elems in the destination buffer (0 or 1: none).
 void build_tile_table(const ew_plan_t &plan, int which, uint32_t tile_elems, uint32_t align_elems,
                       TileTable &out);

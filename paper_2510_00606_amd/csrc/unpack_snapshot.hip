@@ -172,17 +172,16 @@ int launch_pass(const ew::TileTable &tt, uint64_t t0, uint64_t n, const CopyTabs
   return EW_OK;
 }
 
-}  // namespace
-
-extern "C" int ew_unpack_snapshot(const ew_plan_t *plan, const void *stage, const void *const *old_shards,
-                                  const void *const *snapshots, void *const *new_shards, void *const *new_snapshots,
-                                  ew_cksum_t *const *new_cksums, uint32_t elem_size, void *stream_) {
+// which = 1: through the arena (stage); which = 2: every segment straight from its source
+int unpack_snapshot(const ew_plan_t *plan, int which, const void *stage, const void *const *old_shards,
+                    const void *const *snapshots, void *const *new_shards, void *const *new_snapshots,
+                    ew_cksum_t *const *new_cksums, uint32_t elem_size, void *stream_) {
   if (!ew::tables_usable(plan) || (elem_size != 2 && elem_size != 4)) return EW_EINVAL;
   const int e = elem_size == 4 ? 1 : 0;
-  const ew::TileTable &tt = plan->tables[1][e];
+  const ew::TileTable &tt = plan->tables[which][e];
   if (tt.ntiles == 0) return EW_OK;
   if (!new_shards || !new_snapshots || !new_cksums) return EW_EINVAL;
-  if (plan->stage_len > 0 && !stage) return EW_EINVAL;
+  if (which == 1 && plan->stage_len > 0 && !stage) return EW_EINVAL;
   if ((uint64_t)plan->tile_elems[e] * elem_size > EW_CKSUM_BLOCK) return EW_EINVAL;  // a tile spans <= 2 blocks
   hipStream_t stream = (hipStream_t)stream_;
   CopyTabs tabs;
@@ -217,3 +216,22 @@ extern "C" int ew_unpack_snapshot(const ew_plan_t *plan, const void *stage, cons
   }
   return EW_OK;
 }
+
+}  // namespace
+
+extern "C" {
+
+int ew_unpack_snapshot(const ew_plan_t *plan, const void *stage, const void *const *old_shards,
+                       const void *const *snapshots, void *const *new_shards, void *const *new_snapshots,
+                       ew_cksum_t *const *new_cksums, uint32_t elem_size, void *stream) {
+  return unpack_snapshot(plan, 1, stage, old_shards, snapshots, new_shards, new_snapshots, new_cksums, elem_size, stream);
+}
+
+int ew_reshard_snapshot(const ew_plan_t *plan, const void *const *old_shards, const void *const *snapshots,
+                        void *const *new_shards, void *const *new_snapshots, ew_cksum_t *const *new_cksums,
+                        uint32_t elem_size, void *stream) {
+  return unpack_snapshot(plan, 2, nullptr, old_shards, snapshots, new_shards, new_snapshots, new_cksums, elem_size,
+                         stream);
+}
+
+}  // extern "C"

@@ -194,6 +194,15 @@ def reshard_case(old_dp, new_dp, mask, numel, chunk, elem_size, rng, tile_elems=
         assert np.array_equal(np_bits(new[k][:n]), want_new[k]), f"new shard {k} differs"
         assert guard_intact(new[k], n, elem_size)
 
+    # direct form: every segment pulled straight from its source, no arena
+    new_d = [guarded(plan.new_shard_len(k), elem_size) for k in range(new_dp)]
+    ew.ew_reshard(plan, old_dev, snap_dev, new_d, elem_size, stream())
+    torch.cuda.synchronize()
+    for k in range(new_dp):
+        n = plan.new_shard_len(k)
+        assert np.array_equal(np_bits(new_d[k][:n]), want_new[k]), f"direct: new shard {k} differs"
+        assert guard_intact(new_d[k], n, elem_size)
+
     # fused form: unpack + snapshot + checksums of the new shards in one pass
     new2 = [guarded(plan.new_shard_len(k), elem_size) for k in range(new_dp)]
     snap2 = [guarded(plan.new_shard_len(k), elem_size) for k in range(new_dp)]
@@ -215,6 +224,18 @@ def reshard_case(old_dp, new_dp, mask, numel, chunk, elem_size, rng, tile_elems=
         got = ck2[k].cpu().numpy().view(np.uint64)
         assert np.array_equal(got[:nblk[k]], checksum.block_checksums(want_new[k])), f"fused: checksums of {k} differ"
         assert (got[nblk[k]] == np.uint64((1 << 64) - 1)).all(), "record past the end was written"
+    # ... and the same without the arena
+    new3 = [guarded(plan.new_shard_len(k), elem_size) for k in range(new_dp)]
+    snap3 = [guarded(plan.new_shard_len(k), elem_size) for k in range(new_dp)]
+    ck3 = [torch.full((nb + 1, 2), -1, dtype=torch.int64, device=DEV) for nb in nblk]
+    ew.ew_reshard_snapshot(plan, old_dev, snap_dev, new3, snap3, ck3, elem_size, stream())
+    torch.cuda.synchronize()
+    for k in range(new_dp):
+        n = plan.new_shard_len(k)
+        assert np.array_equal(np_bits(new3[k][:n]), want_new[k]), f"direct fused: new shard {k} differs"
+        assert np.array_equal(np_bits(snap3[k][:n]), want_new[k]), f"direct fused: snapshot of new shard {k} differs"
+        assert guard_intact(new3[k], n, elem_size) and guard_intact(snap3[k], n, elem_size)
+        assert torch.equal(ck3[k], ck2[k]), f"direct fused: checksums of {k} differ"
     plan.close()
 
 

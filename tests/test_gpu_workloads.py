@@ -12,7 +12,8 @@
                       integer ops)
 Every workload also runs the fused ew_unpack_snapshot: new shards and snapshot copies equal the
 verified result, checksums equal the oracle's (all blocks where the oracle result is on the host,
-sampled blocks otherwise).
+sampled blocks otherwise); and the arena-free ew_reshard / ew_reshard_snapshot, whose outputs must
+equal those verified ones.
 """
 import gc
 
@@ -131,6 +132,21 @@ def run_workload_array(w, arr, plan, starts, full_compare, snapshot_all):
             for b in sorted({0, nb - 1} | set(rng.integers(0, nb, 48).tolist())):
                 host = raw[b << 20:min((b + 1) << 20, raw.numel())].cpu().numpy()
                 assert np.array_equal(got[b], checksum.block_checksums(host)[0]), f"{w.name} {arr}: rank {k} block {b}"
+    # (5) without the arena: every segment straight from its source, alone and fused with the snapshot
+    for t in new2 + snap2:
+        t.view(torch.uint8).fill_(0x3C)
+    ew.ew_reshard(plan, old, snaps, new2, es, st)
+    torch.cuda.synchronize()
+    view = torch.int16 if es == 2 else torch.int32
+    for k in range(w.new_dp):
+        assert torch.equal(new2[k].view(view), new[k].view(view)), f"{w.name} {arr}: direct new shard {k} differs"
+        new2[k].view(torch.uint8).fill_(0x3C)
+    ck3 = [torch.full_like(c, -1) for c in ck2]
+    ew.ew_reshard_snapshot(plan, old, snaps, new2, snap2, ck3, es, st)
+    torch.cuda.synchronize()
+    for k in range(w.new_dp):
+        assert torch.equal(new2[k].view(view), new[k].view(view)) and torch.equal(snap2[k].view(view), new[k].view(view))
+        assert torch.equal(ck3[k], ck2[k]), f"{w.name} {arr}: direct fused checksums of rank {k} differ"
     del old, snaps, stage, new, new2, snap2, want_new
     free()
 

@@ -263,7 +263,7 @@ def seg_records(segs, which):
         if which == 0:
             if not local:
                 out.append((data, int(s["src_off"]), 64, int(s["stage_off"]), int(s["len"])))
-        elif local:
+        elif local or which == 2:   # direct: every segment straight from its source
             out.append((data, int(s["src_off"]), int(s["dst_rank"]), int(s["dst_off"]), int(s["len"])))
         else:
             out.append((128, int(s["stage_off"]), int(s["dst_rank"]), int(s["dst_off"]), int(s["len"])))
@@ -272,7 +272,7 @@ def seg_records(segs, which):
 
 def check_tiles(p, tile_elems, align=0):
     segs = p.segs()
-    for which in (0, 1):
+    for which in (0, 1, 2):
         t = p.tiles(which, tile_elems, align)
         assert (t["len"] > 0).all() and (t["len"] <= tile_elems).all()
         got = expand([(int(x["src_buf"]), int(x["src_off"]), int(x["dst_buf"]), int(x["dst_off"]), int(x["len"]))
