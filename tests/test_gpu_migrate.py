@@ -1,5 +1,6 @@
 """GPU parity of layer-migration plans (Sec. 6.3): ew_plan_migrate executed by ew_pack / ew_unpack /
-ew_unpack_snapshot against oracle/migrate.py, both ZeRO assignments, bit for bit."""
+ew_unpack_snapshot and by the arena-free ew_reshard against oracle/migrate.py, both ZeRO assignments,
+bit for bit."""
 import numpy as np
 import pytest
 import torch
@@ -33,6 +34,8 @@ def run_case(assignment, D, src, dst, n_move, elem_size, rng):
     ck2 = [torch.zeros((ew.num_blocks(plan.new_shard_len(k) * elem_size), 2), dtype=torch.int64, device=DEV)
            for k in range(2 * D)]
     ew.ew_unpack_snapshot(plan, stage, old, None, new2, snap2, ck2, elem_size, stream())
+    new3 = [guarded(plan.new_shard_len(k), elem_size) for k in range(2 * D)]
+    ew.ew_reshard(plan, old, None, new3, elem_size, stream())   # no arena: rank j of stage S+1 pulls from rank j of stage S
     torch.cuda.synchronize()
     m = migrate.traffic(src, dst, D, assignment, n_move)
     assert plan.stage_len == int(m.sum() - np.trace(m))
@@ -40,7 +43,7 @@ def run_case(assignment, D, src, dst, n_move, elem_size, rng):
     for k in range(2 * D):
         n = plan.new_shard_len(k)
         assert n == len(want[k])
-        for got in (new[k], new2[k], snap2[k]):
+        for got in (new[k], new2[k], snap2[k], new3[k]):
             assert np.array_equal(np_bits(got[:n]), want[k]), f"rank {k} differs"
             assert guard_intact(got, n, elem_size)
         assert np.array_equal(ck2[k].cpu().numpy().view(np.uint64), checksum.block_checksums(want[k]))
