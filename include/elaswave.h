@@ -171,7 +171,7 @@ int ew_plan_tiles(const ew_plan_t *plan, int which, uint32_t tile_elems, uint32_
 
 /* Builds the copy-tile tables (segments cut into pieces of at most tile_elems elements;
  * 0 = library default, 4 KiB worth of elements) for both element sizes and uploads them to the
- * current device on `stream` (a few KiB for a uniform chunk).  Must precede ew_pack /
+ * current device on `stream` (a few hundred KiB for a uniform chunk).  Must precede ew_pack /
  * ew_unpack, which return EW_EINVAL when another device is current than the one the tables
  * were uploaded to.  Calling it again replaces the tables (previous work must be done).
  * EW_EINVAL if a table would exceed 2^31-1 tiles. */
