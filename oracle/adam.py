@@ -45,7 +45,8 @@ def grad_to_f32(g: np.ndarray) -> np.ndarray:
 
 
 def bf16_bits(w: np.ndarray) -> np.ndarray:
-    """Round-to-nearest-even fp32 -> bf16 through torch's conversion routine."""
+    """Round-to-nearest-even fp32 -> bf16 through torch's conversion routine (pinned by a hand-worked
+    table of bit patterns and an integer-only rule in the tests, not by calling torch again)."""
     return torch.from_numpy(np.ascontiguousarray(w)).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
 
 

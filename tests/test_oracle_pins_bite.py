@@ -36,7 +36,10 @@ MIGRATE_PINS = [
 ADAM_PINS = [
     TA.test_first_step_closed_form, TA.test_zero_gradient_decays_moments_and_applies_weight_decay_only,
     TA.test_against_float64_and_torch_adamw, TA.test_bf16_gradient_widens_exactly, TA.test_hyper_scalars,
+    TA.test_bf16_rounding_by_hand, TA.test_bf16_rounding_matches_integer_rule_on_random_bits,
 ]
+# the pins of the bf16 rounding that call no conversion routine of any library
+BF16_PINS = [TA.test_bf16_rounding_by_hand, TA.test_bf16_rounding_matches_integer_rule_on_random_bits]
 PARTITION_PINS = [TP.test_oracle_closed_forms]   # the one that involves the oracle alone
 
 
@@ -194,6 +197,37 @@ def _adam_variant(**change):
 
 def _bf16_truncate(w):
     return (np.ascontiguousarray(w).view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+
+
+def _bf16_half_away(w):        # ties away from zero: add half a unit to the magnitude, then truncate
+    u = np.ascontiguousarray(w).view(np.uint32).astype(np.uint64)
+    return ((u + np.uint64(0x8000)) >> np.uint64(16)).astype(np.uint16)
+
+
+def _bf16_half_up(w):          # ties toward +infinity: away from zero for positives, toward zero for negatives
+    u = np.ascontiguousarray(w).view(np.uint32).astype(np.uint64)
+    neg = (u >> np.uint64(31)) == 1
+    return ((u + np.where(neg, np.uint64(0x7FFF), np.uint64(0x8000))) >> np.uint64(16)).astype(np.uint16)
+
+
+def _bf16_half_odd(w):         # ties to the odd neighbour
+    u = np.ascontiguousarray(w).view(np.uint32).astype(np.uint64)
+    return ((u + np.uint64(0x8000) - ((u >> np.uint64(16)) & np.uint64(1))) >> np.uint64(16)).astype(np.uint16)
+
+
+BF16_MISTAKES = {
+    "bf16 by truncation": _bf16_truncate,
+    "bf16 ties away from zero": _bf16_half_away,
+    "bf16 ties toward plus infinity": _bf16_half_up,
+    "bf16 ties to odd": _bf16_half_odd,
+}
+
+
+@pytest.mark.parametrize("name", sorted(BF16_MISTAKES))
+def test_bf16_pins_catch_without_any_library_conversion(name, monkeypatch):
+    monkeypatch.setattr(adam, "bf16_bits", BF16_MISTAKES[name])
+    for pin in BF16_PINS:       # each of the two pins notices each mistake on its own
+        assert failures([pin]) == 1, f"{pin.__name__} does not notice: {name}"
 
 
 ADAM_MISTAKES = {
