@@ -2,8 +2,8 @@
 
 TEST INFRASTRUCTURE ONLY (see oracle/__init__.py).
 
-The paper says snapshots "support online verification" (abstract) without
-defining the check.  Definition used here: the buffer's bytes are read as
+The abstract names verification of the snapshots while training runs, and the
+paper never defines the check.  Definition used here: the buffer's bytes are read as
 little-endian 64-bit words (a trailing partial word is zero-padded); block b
 covers bytes [b*2^20, min((b+1)*2^20, nbytes)); its record is
 (sum of its words mod 2^64, XOR of its words).  Both are order-independent,

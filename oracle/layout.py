@@ -15,7 +15,7 @@ Readings taken where the paper is silent (each is restated in the repo's
 design notes):
   * unit = the paper's "layer": a run of consecutive elements of the flat
     state given by explicit boundaries (uniform `chunk`, last unit short).
-  * "uniformly partitioned" with a remainder: boundaries are the floor split
+  * a unit whose length the DP degree does not divide: boundaries are the floor split
     of the unit's 8-element granules, b_j = min(L, 8*floor(j*ceil(L/8)/D)).
   * survivors keep their relative order and are renumbered densely from 0;
     joiners are appended; if fewer new ranks than survivors, the highest
@@ -41,7 +41,7 @@ def piece_bounds(L: int, D: int) -> list[int]:
     """Boundaries b_0..b_D of one unit of L elements split over D ranks.
 
     Rank j owns [b_j, b_{j+1}) of the unit.  Every rank owns a piece of every
-    unit (Fig. 10b: "rank j owns the j-th shard O_i^j for every layer").
+    unit: its shard number j of each of them (Sec. 6.3, Fig. 10b).
     """
     if D < 1 or L < 0:
         raise ValueError("bad unit/degree")
