@@ -174,6 +174,9 @@ int ew_plan_tiles(const ew_plan_t *plan, int which, uint32_t tile_elems, uint32_
  * current device on `stream` (a few hundred KiB for a uniform chunk).  Must precede ew_pack /
  * ew_unpack, which return EW_EINVAL when another device is current than the one the tables
  * were uploaded to.  Calling it again replaces the tables (previous work must be done).
+ * The copy is asynchronous on `stream`: calls that use the plan must be ordered after it, i.e. be
+ * issued on the same stream, or on another one only after `stream` has been synchronised (or after
+ * an event recorded on it behind this call has been waited for).
  * EW_EINVAL if a table would exceed 2^31-1 tiles. */
 int ew_plan_upload(ew_plan_t *plan, uint32_t tile_elems, void *stream);
 
@@ -203,8 +206,9 @@ int ew_unpack(const ew_plan_t *plan, const void *stage, const void *const *old_s
  * read once: it is stored to the new shard and to its snapshot copy and folded into the checksum
  * of the new shard's 1 MiB block it lands in.  new_snapshots, new_cksums: host arrays of new_dp
  * device pointers (buffers of new_len[k]*elem_size bytes / ceil(that / 2^20) records, records
- * overwritten).  Uses the library's scratch array like ew_snapshot: EW_ENOMEM only for a stream
- * under graph capture that owns no scratch region yet (run the call once on it before capturing);
+ * overwritten).  Uses the library's scratch array like ew_snapshot, and like it has a slower form
+ * that needs no scratch (every workgroup adds its tile to the records with atomics) for a stream
+ * under graph capture that can get no region; see ew_snapshot for the rules.
  * EW_EINVAL if the plan was uploaded with tiles above 1 MiB. */
 int ew_unpack_snapshot(const ew_plan_t *plan, const void *stage, const void *const *old_shards,
                        const void *const *snapshots, void *const *new_shards, void *const *new_snapshots,
@@ -213,7 +217,8 @@ int ew_unpack_snapshot(const ew_plan_t *plan, const void *stage, const void *con
 /* ---- Live Remap steps 3 and 4 without the arena ------------------------------------------------
  * Where holders and destinations share one address space -- all ranks in one GPU's memory as here,
  * or load/store-mapped peers -- a destination can pull every segment straight from the holder's
- * live shard or snapshot (Fig. 7a: "pulls from DP 1's device", "from DP 1's host snapshot") and
+ * live shard or snapshot (the two kinds of pull that Fig. 7a's caption names: from a survivor's
+ * device memory and from the snapshot a survivor keeps of its failed neighbour) and
  * the pair messages need not be materialised: new_shards as after ew_pack + ew_unpack, 28 B per
  * element of traffic less for every remote element.  ew_reshard_snapshot adds the snapshot copies
  * and checksums of the new shards exactly as ew_unpack_snapshot does.  Arguments, errors and
@@ -232,14 +237,23 @@ int ew_reshard_snapshot(const ew_plan_t *plan, const void *const *old_shards, co
  * Never allocates device memory: per-workgroup partial checksums go through a fixed scratch array
  * inside the library (128 MiB per device, 4 regions).  A stream keeps the region it used last; when
  * more than 4 streams take turns, the least recently used region changes hands and the new stream
- * is made to wait (on the device, not the host) for that region's last use.  Buffers that are not
- * 16-byte aligned, and a stream under graph capture that owns no region yet (run the calls once on
- * it before capturing), use a slower kernel that needs no scratch.  A region that a captured graph
- * uses stays with the capturing stream for good (the graph's replays are invisible to the
- * library): replay such a graph on the stream it was captured on, or ordered after that stream's
- * other calls, and capture on at most 4 streams per device.  Calls may be issued from several
- * host threads. */
+ * is made to wait (on the device, not the host) for that region's last use.  Calls may be issued
+ * from several host threads, also on one stream; calls on different streams are enqueued side by
+ * side.  Buffers that are not 16-byte aligned use a slower kernel that needs no scratch.
+ * Graph capture: a capturing stream can use a region it already owns (run the calls once on it
+ * before capturing) or one that no stream has used yet.  A region that a captured graph uses stays
+ * with the capturing stream (the graph's replays are invisible to the library) until
+ * ew_scratch_release: replay such a graph on the stream it was captured on, or ordered after that
+ * stream's other calls.  One region per device always stays outside graphs, so at most 3 streams
+ * per device capture with scratch; a capture that can get no region (a fourth capturing stream, or
+ * one whose warm-up region went to another stream meanwhile) records the slower scratch-free
+ * kernels instead, with the same results. */
 int ew_snapshot(const void *src, void *dst, uint64_t nbytes, ew_cksum_t *cksums, void *stream);
+
+/* Tells the library that every graph captured on `stream` (on the current device) has been
+ * destroyed and its replays are complete: the scratch regions those graphs used may change hands
+ * again.  Harmless when there is nothing to release. */
+int ew_scratch_release(void *stream);
 
 /* ---- Integrity check of stored bytes (Live Remap step 1) ----------------------------------
  * Recomputes the block checksums of buf into got[] (device, ceil(nbytes/2^20) records,
@@ -300,13 +314,16 @@ int ew_checksum_host(const void *buf, uint64_t nbytes, ew_cksum_t *cksums, uint3
  * 16 and at most (2^31-1) KiB, else EW_EINVAL. */
 int ew_memcpy(const void *src, void *dst, uint64_t nbytes, void *stream);
 
-/* Launch-shape knobs for benchmarking sweeps (process-wide, not thread-safe; defaults are the
- * tuned ones).  Names: "tile_bytes", "tile_elems", "tile_align_bytes", "cksum_sub_bytes",
+/* Launch-shape knobs for benchmarking sweeps (process-wide; each is read and written atomically,
+ * so setting one while other threads launch is safe; defaults are the tuned ones).  Names: "tile_bytes", "tile_elems", "tile_align_bytes", "cksum_sub_bytes",
  * "cksum_wgs_per_cu", "cksum_mode" (-1 = default: slot kernel + fold for ew_snapshot, atomic kernel
  * for ew_verify; 0 / 1 force the slot / atomic kernel for both), "snapshot_wave_min_bytes"
  * (ew_snapshot uses one-wave workgroups from this size on, 256-lane ones below; default 128 MiB),
  * "fused_wgs_per_cu", "verify_wgs_per_cu", "adam_wgs_per_cu" (workgroups resident per CU for the
- * kernels of ew_unpack_snapshot, ew_verify and ew_adam_step; 0 = all that fit; defaults 6, 4, 11).
+ * kernels of ew_unpack_snapshot, ew_verify and ew_adam_step; 0 = all that fit; defaults 6, 4, 11),
+ * "fused_mode" (0 = default; 1 forces the scratch-free form of ew_unpack_snapshot),
+ * "scratch_max_concurrent" (read-only statistic: the most calls that ever held a scratch region at
+ * the same time; setting it to 0 resets it).
  * Returns EW_EINVAL for an unknown name or an out-of-range value. */
 int ew_set_param(const char *name, int64_t value);
 int64_t ew_get_param(const char *name);

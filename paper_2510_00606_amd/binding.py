@@ -71,6 +71,7 @@ _SIGNATURES = {
     "ew_reshard_snapshot": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32,
                                       C.c_void_p]),
     "ew_snapshot": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]),
+    "ew_scratch_release": (C.c_int, [C.c_void_p]),
     "ew_verify": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                             C.c_uint64, C.c_void_p]),
     "ew_single_bit_flip": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint32), C.POINTER(C.c_int32)]),
@@ -363,6 +364,10 @@ def ew_snapshot(src, dst, nbytes: int, cksums, stream=None):
         if n is not None and n < need:
             raise ValueError(f"{name} holds {n} bytes, call needs {need}")
     _check(lib().ew_snapshot(_ptr(src), _ptr(dst), nbytes, _ptr(cksums), _stream(stream)), "ew_snapshot")
+
+
+def ew_scratch_release(stream=None):
+    _check(lib().ew_scratch_release(_stream(stream)), "ew_scratch_release")
 
 
 def ew_verify(buf, nbytes: int, expect, got, n_bad, bad_blocks, diffs, cap: int, stream=None):

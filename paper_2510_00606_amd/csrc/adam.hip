@@ -146,20 +146,30 @@ int run_threads(uint64_t n_items, uint32_t n_threads, Fn fn) {  // fn(lo, hi) on
     fn((uint64_t)0, n_items);
     return EW_OK;
   }
+  // The pool outlives the try block: if a thread cannot be started, those already running are joined
+  // and the calling thread does the ranges that are left, so the work is still done exactly once.
+  std::vector<std::thread> pool;
+  const uint64_t per = (n_items + n_threads - 1) / n_threads;
+  uint64_t next = 0;  // first item no thread has been given
+  int rc = EW_OK;
   try {
-    std::vector<std::thread> pool;
-    const uint64_t per = (n_items + n_threads - 1) / n_threads;
-    for (uint32_t t = 0; t < n_threads; ++t) {
-      const uint64_t lo = std::min<uint64_t>(n_items, (uint64_t)t * per), hi = std::min<uint64_t>(n_items, lo + per);
-      if (lo < hi) pool.emplace_back(fn, lo, hi);
+    pool.reserve(n_threads);
+    while (next < n_items) {
+      const uint64_t hi = std::min<uint64_t>(n_items, next + per);
+      pool.emplace_back(fn, next, hi);
+      next = hi;
     }
-    for (auto &th : pool) th.join();
   } catch (const std::bad_alloc &) {
-    return EW_ENOMEM;
+    rc = EW_ENOMEM;
   } catch (const std::system_error &) {
-    return EW_ENOMEM;
+    rc = EW_ENOMEM;
   }
-  return EW_OK;
+  if (rc != EW_OK && next < n_items) {
+    fn(next, n_items);
+    rc = EW_OK;
+  }
+  for (auto &th : pool) th.join();
+  return rc;
 }
 
 }  // namespace
@@ -223,10 +233,10 @@ int ew_grad_ship(const void *grad_dev, void *peer_dev, void *host_buf, uint64_t 
   hipStream_t s = (hipStream_t)stream;
   const void *from = grad_dev;
   if (peer_dev) {  // device-to-device hop to the worker that keeps the snapshot
-    if (hipMemcpyAsync(peer_dev, grad_dev, nbytes, hipMemcpyDeviceToDevice, s) != hipSuccess) return EW_EHIP;
+    EW_HIP(hipMemcpyAsync(peer_dev, grad_dev, nbytes, hipMemcpyDeviceToDevice, s));
     from = peer_dev;
   }
-  if (host_buf && hipMemcpyAsync(host_buf, from, nbytes, hipMemcpyDeviceToHost, s) != hipSuccess) return EW_EHIP;
+  if (host_buf) EW_HIP(hipMemcpyAsync(host_buf, from, nbytes, hipMemcpyDeviceToHost, s));
   return EW_OK;
 }
 

@@ -244,21 +244,14 @@ int launch_cksum_streaming(const void *src, void *dst, uint64_t nbytes, ew_cksum
   return EW_OK;
 }
 
+// Slot kernel + fold kernel over `slots` (room for max_slots of them), in as many passes as that takes.
 template <bool COPY>
-int launch_cksum(const void *src, void *dst, uint64_t nbytes, ew_cksum_t *out, hipStream_t stream) {
-  const bool aligned = ((((uintptr_t)src) | (COPY ? (uintptr_t)dst : 0)) & 15u) == 0;
-  // Read-only passes (verify) keep the streaming kernel: with no stores for the fold to hide behind,
-  // one slot per KiB is the slower shape for them.
-  const int64_t mode = ew::knobs().cksum_mode >= 0 ? ew::knobs().cksum_mode : (COPY ? 0 : 1);
-  if (!aligned || mode != 0) return launch_cksum_streaming<COPY>(src, dst, nbytes, out, stream);
-  // the (slot kernel, fold kernel) pairs of one call must reach the stream back to back
-  ew::ScratchLease lease(stream);
-  ew_cksum_t *slots = lease.slots();
-  if (!slots) return launch_cksum_streaming<COPY>(src, dst, nbytes, out, stream);  // needs no scratch
+int launch_cksum_slots(const void *src, void *dst, uint64_t nbytes, ew_cksum_t *out, ew_cksum_t *slots,
+                       uint64_t max_slots, hipStream_t stream) {
   // one slot per KiB (one-wave workgroups) from snapshot_wave_min_bytes on, one per 4 KiB below
   const bool one_wave = nbytes >= (uint64_t)ew::knobs().snapshot_wave_min_bytes;
   const uint64_t slot_bytes = one_wave ? 1024 : 4096;
-  const uint64_t pass_bytes = ew::kRegionSlots * slot_bytes;  // what one region's slots cover
+  const uint64_t pass_bytes = max_slots * slot_bytes;  // what the slots cover; a multiple of 1 MiB
   for (uint64_t off = 0; off < nbytes; off += pass_bytes) {
     const uint64_t n = nbytes - off < pass_bytes ? nbytes - off : pass_bytes;
     // a partial trailing vector belongs to lane n/16, which the last workgroup always contains because
@@ -277,6 +270,21 @@ int launch_cksum(const void *src, void *dst, uint64_t nbytes, ew_cksum_t *out, h
     EW_HIP(hipGetLastError());
   }
   return EW_OK;
+}
+
+template <bool COPY>
+int launch_cksum(const void *src, void *dst, uint64_t nbytes, ew_cksum_t *out, hipStream_t stream) {
+  const bool aligned = ((((uintptr_t)src) | (COPY ? (uintptr_t)dst : 0)) & 15u) == 0;
+  // Read-only passes (verify) keep the streaming kernel: with no stores for the fold to hide behind,
+  // one slot per KiB is the slower shape for them.
+  const int64_t knob = ew::knobs().cksum_mode;
+  const int64_t mode = knob >= 0 ? knob : (COPY ? 0 : 1);
+  if (!aligned || mode != 0) return launch_cksum_streaming<COPY>(src, dst, nbytes, out, stream);
+  // the lease keeps other calls off the region until this call's last kernel has been enqueued
+  ew::ScratchLease lease(stream);
+  ew_cksum_t *slots = lease.slots();
+  if (!slots) return launch_cksum_streaming<COPY>(src, dst, nbytes, out, stream);  // needs no scratch
+  return launch_cksum_slots<COPY>(src, dst, nbytes, out, slots, ew::kRegionSlots, stream);
 }
 
 }  // namespace

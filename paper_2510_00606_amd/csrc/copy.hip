@@ -123,7 +123,8 @@ uint64_t ew_plan_num_tiles(const ew_plan_t *plan, int which, uint32_t elem_size)
   const int e = elem_size == 4 ? 1 : 0;
   if (plan->uploaded) return plan->tables[which][e].ntiles;
   const ew::Knobs &k = ew::knobs();
-  const uint32_t te = k.tile_elems > 0 ? (uint32_t)k.tile_elems : (uint32_t)(k.tile_bytes / elem_size);
+  const int64_t knob_elems = k.tile_elems;
+  const uint32_t te = knob_elems > 0 ? (uint32_t)knob_elems : (uint32_t)(k.tile_bytes / elem_size);
   try {
     ew::TileTable tt;
     ew::build_tile_table(*plan, which, te, (uint32_t)(k.tile_align_bytes / elem_size), tt);
@@ -138,15 +139,16 @@ int ew_plan_upload(ew_plan_t *plan, uint32_t tile_elems, void *stream) {
   if (tile_elems > (1u << 24)) return EW_EINVAL;
   release_tables(plan);
   const ew::Knobs &k = ew::knobs();
-  if (tile_elems == 0 && k.tile_elems > 0) tile_elems = (uint32_t)k.tile_elems;
+  const int64_t knob_elems = k.tile_elems, knob_bytes = k.tile_bytes, knob_align = k.tile_align_bytes;
+  if (tile_elems == 0 && knob_elems > 0) tile_elems = (uint32_t)knob_elems;
   size_t bytes = 0;
   try {
     for (int e = 0; e < 2; ++e) {
       const uint32_t es = e ? 4u : 2u;
-      plan->tile_elems[e] = tile_elems ? tile_elems : (uint32_t)(k.tile_bytes / es);
+      plan->tile_elems[e] = tile_elems ? tile_elems : (uint32_t)(knob_bytes / es);
       for (int w = 0; w < ew::kNumTables; ++w) {
         ew::TileTable &tt = plan->tables[w][e];
-        ew::build_tile_table(*plan, w, plan->tile_elems[e], (uint32_t)(k.tile_align_bytes / es), tt);
+        ew::build_tile_table(*plan, w, plan->tile_elems[e], (uint32_t)(knob_align / es), tt);
         if (tt.ntiles > 0x7fffffffull) {  // tile ids are workgroup ids
           release_tables(plan);
           return EW_EINVAL;

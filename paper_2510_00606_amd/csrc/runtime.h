@@ -4,6 +4,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdint>
 #include <mutex>
 
@@ -21,22 +22,26 @@ const char *last_hip_error();
     if (e__ != hipSuccess) return ::ew::hip_fail(e__, #call); \
   } while (0)
 
-// Launch-shape knobs behind ew_set_param / ew_get_param.
+// Launch-shape knobs behind ew_set_param / ew_get_param.  Each is an atomic of its own, so a launch
+// on one host thread may read them while another thread sets one; a call reads every knob it needs
+// once, so it never sees two values of the same knob.
+typedef std::atomic<int64_t> Knob;
 struct Knobs {
-  int64_t cksum_sub_bytes = 65536;  // streaming checksum kernel: bytes of a block per workgroup pass
-  int64_t cksum_wgs_per_cu = 0;     // streaming checksum kernel: 0 = one workgroup per sub-block,
-                                    // else a persistent grid of this many workgroups per CU
-  int64_t cksum_mode = -1;          // -1 = slot kernel + fold for snapshot, streaming kernel for verify;
-                                    // 0 / 1 force the slot / streaming kernel for both
-  int64_t snapshot_wave_min_bytes = 128 << 20;  // snapshot: one-wave workgroups from this size on, 256 lanes below
-  int64_t tile_bytes = 4096;        // default copy tile: 256 lanes x one 128-bit vector
-  int64_t tile_elems = 0;           // > 0 overrides tile_bytes with a size in elements
-  int64_t tile_align_bytes = 128;   // tile cuts fall on multiples of this in the destination (0: off)
+  Knob cksum_sub_bytes{65536};  // streaming checksum kernel: bytes of a block per workgroup pass
+  Knob cksum_wgs_per_cu{0};     // streaming checksum kernel: 0 = one workgroup per sub-block,
+                                // else a persistent grid of this many workgroups per CU
+  Knob cksum_mode{-1};          // -1 = slot kernel + fold for snapshot, streaming kernel for verify;
+                                // 0 / 1 force the slot / streaming kernel for both
+  Knob snapshot_wave_min_bytes{128 << 20};  // snapshot: one-wave workgroups from this size on, 256 lanes below
+  Knob tile_bytes{4096};        // default copy tile: 256 lanes x one 128-bit vector
+  Knob tile_elems{0};           // > 0 overrides tile_bytes with a size in elements
+  Knob tile_align_bytes{128};   // tile cuts fall on multiples of this in the destination (0: off)
   // Caps on the workgroups resident per CU (0 = all that fit) for the kernels that keep three or more
   // HBM streams busy, or that read only: they run faster with fewer requests in flight.
-  int64_t fused_wgs_per_cu = 6;     // fused unpack + snapshot (256 lanes; 8 fit)
-  int64_t verify_wgs_per_cu = 4;    // read-only streaming checksum (256 lanes; 8 fit)
-  int64_t adam_wgs_per_cu = 11;     // optimizer step (one wave per workgroup; 32 fit)
+  Knob fused_wgs_per_cu{6};     // fused unpack + snapshot (256 lanes; 8 fit)
+  Knob fused_mode{0};           // fused unpack + snapshot: 0 = slot per tile + fold kernel, 1 = scratch-free (atomics)
+  Knob verify_wgs_per_cu{4};    // read-only streaming checksum (256 lanes; 8 fit)
+  Knob adam_wgs_per_cu{11};     // optimizer step (one wave per workgroup; 32 fit)
 };
 Knobs &knobs();
 
@@ -57,18 +62,26 @@ int launch_zero(void *p, uint64_t nbytes, hipStream_t stream);
 // the least recently used region changes hands, and the new owner's stream is first made to wait
 // (hipStreamWaitEvent, no host blocking) for the event recorded after the region's last use, so
 // two streams never touch a region at once.  A stream under graph capture can only use a region it
-// already owns (its warm-up run claims one); such a region stays with that stream for good, because
-// replays of the graph use it unseen.  One region (32 MiB) holds 2^21 slots: 2 GiB of
-// input for the snapshot kernel (one slot per wave and KiB), 2^21 tiles for the fused unpack (one slot
-// per tile); longer inputs take several passes.
+// already owns or one nobody has used yet; such a region stays with that stream (replays of the
+// graph use it unseen) until ew_scratch_release says the graphs are gone, and one region per device
+// always stays outside graphs so that eager calls on other streams keep working: the capture that
+// would take the last one gets no region and its caller takes the scratch-free kernel instead.
+// One region (32 MiB) holds 2^21 slots: 2 GiB of input for the snapshot kernel (one slot per wave and
+// KiB), 2^21 tiles for the fused unpack (one slot per tile); longer inputs take several passes.
+//
+// Locking: one mutex per device, held only while a region is picked and while its hand-over event is
+// recorded, never while kernels are enqueued.  A region is marked busy in between, so two host
+// threads that share a stream get two regions (their kernel pairs may then interleave on the stream
+// without touching each other's slots), and calls on different streams or devices enqueue at the
+// same time.
 constexpr uint32_t kRegions = 4;
 constexpr uint64_t kRegionSlots = 1ull << 21;
 struct Region;
-// A call's hold on a region.  The constructor takes the scratch lock and a region for `stream`; the
+struct DeviceScratch;
+// A call's hold on a region.  The constructor picks a region for `stream` and marks it busy; the
 // destructor (also on an early error return) records the event that later hand-overs wait for and
-// drops the lock, so the kernels of one call reach the stream back to back and a region never
-// changes hands without that event.  slots() is the region's device address, nullptr when none can
-// be had.
+// clears the mark.  slots() is the region's device address, nullptr when none can be had (a stream
+// under capture as described above, or a failing HIP call).
 class ScratchLease {
  public:
   explicit ScratchLease(hipStream_t stream);
@@ -78,11 +91,17 @@ class ScratchLease {
   ew_cksum_t *slots() const { return slots_; }
 
  private:
-  std::unique_lock<std::mutex> lock_;
   hipStream_t stream_;
+  DeviceScratch *dev_ = nullptr;
   Region *region_ = nullptr;
   ew_cksum_t *slots_ = nullptr;
+  bool capturing_ = false;
 };
+
+// The most leases ever held at once in this process (optionally reset to 0), and the call behind
+// ew_scratch_release.
+int64_t scratch_max_concurrent(bool reset);
+int scratch_release(hipStream_t stream);
 
 // ---- pointer tables of the tile-driven kernels, passed by value ----------------------------------
 struct CopyTabs {

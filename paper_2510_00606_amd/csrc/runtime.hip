@@ -4,6 +4,7 @@
 #include "runtime.h"
 
 #include <atomic>
+#include <condition_variable>
 #include <cstring>
 #include <string>
 
@@ -32,21 +33,27 @@ constexpr int kMaxDevices = 64;
 struct Region {
   hipStream_t owner = nullptr;
   bool taken = false;
+  bool busy = false;          // a host thread is between picking it and recording its event
   hipEvent_t done = nullptr;  // recorded on the owner's stream after each use
   bool recorded = false;
-  bool in_graph = false;  // some captured graph uses it: its replays are invisible here, so it never changes hands
+  bool in_graph = false;  // some captured graph uses it: its replays are invisible here, so it does not change hands
   uint64_t last_use = 0;
+};
+
+struct DeviceScratch {
+  std::mutex mu;
+  std::condition_variable freed;  // a busy region was given back
+  ew_cksum_t *base = nullptr;     // address of this device's copy of the array
+  Region region[kRegions];
+  uint64_t clock = 0;
 };
 
 namespace {
 
-struct ScratchState {
-  std::mutex mu;
-  ew_cksum_t *base[kMaxDevices] = {nullptr};  // per device: address of that device's copy of the array
-  Region region[kMaxDevices][kRegions];
-  uint64_t clock = 0;
-};
-ScratchState g_scratch;
+DeviceScratch g_scratch[kMaxDevices];
+// leases held right now over all devices, and the most ever held at once (ew_get_param
+// "scratch_max_concurrent"): shows that calls on different streams enqueue side by side
+std::atomic<int64_t> g_leases{0}, g_leases_max{0};
 
 bool stream_is_capturing(hipStream_t stream) {
   hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
@@ -61,6 +68,7 @@ bool stream_is_capturing(hipStream_t stream) {
 
 int hip_fail(hipError_t e, const char *what) {
   g_hip_error = std::string(what) + ": " + hipGetErrorString(e);
+  (void)hipGetLastError();  // reported here: the runtime's own record of it must not surface in a later call
   return EW_EHIP;
 }
 
@@ -118,74 +126,122 @@ int launch_zero(void *p, uint64_t nbytes, hipStream_t stream) {
   return EW_OK;
 }
 
-namespace {
-
-// Caller holds g_scratch.mu.  Returns the region's device address (the region through *out), or
-// nullptr when none can be had.
-ew_cksum_t *acquire_region(hipStream_t stream, Region **out) {
+ScratchLease::ScratchLease(hipStream_t stream) : stream_(stream) {
   int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
-  if (!g_scratch.base[dev]) {
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    (void)hipGetLastError();
+    return;
+  }
+  DeviceScratch &ds = g_scratch[dev];
+  std::unique_lock<std::mutex> lock(ds.mu);
+  if (!ds.base) {
     void *p = nullptr;
     if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_slot_scratch)) != hipSuccess || !p) {
       (void)hipGetLastError();
-      return nullptr;
+      return;
     }
-    g_scratch.base[dev] = (ew_cksum_t *)p;
+    ds.base = (ew_cksum_t *)p;
   }
-  Region *reg = g_scratch.region[dev];
-  int pick = -1;
+  capturing_ = stream_is_capturing(stream);
   // hipStreamPerThread names a different stream in every host thread, so it never owns a region:
-  // each of its calls goes through the event-ordered handover below
+  // each of its calls goes through the event-ordered hand-over below
   const bool ownable = stream != hipStreamPerThread;
-  for (uint32_t r = 0; r < kRegions && pick < 0 && ownable; ++r)
-    if (reg[r].taken && reg[r].owner == stream) pick = (int)r;
-  for (uint32_t r = 0; r < kRegions && pick < 0; ++r)
-    if (!reg[r].taken) pick = (int)r;
-  if (pick < 0) {
-    if (stream_is_capturing(stream)) return nullptr;  // cannot order a capture after outside work
-    for (uint32_t r = 0; r < kRegions; ++r)
-      if (!reg[r].in_graph && (pick < 0 || reg[r].last_use < reg[pick].last_use)) pick = (int)r;
-    if (pick < 0) return nullptr;  // every region belongs to a captured graph
-    if (reg[pick].recorded && hipStreamWaitEvent(stream, reg[pick].done, 0) != hipSuccess) {
-      (void)hipGetLastError();
-      return nullptr;
+  Region *reg = ds.region;
+  int pick = -1;
+  for (;;) {
+    for (uint32_t r = 0; r < kRegions && pick < 0 && ownable; ++r)
+      if (reg[r].taken && !reg[r].busy && reg[r].owner == stream) pick = (int)r;
+    for (uint32_t r = 0; r < kRegions && pick < 0; ++r)
+      if (!reg[r].taken) pick = (int)r;
+    if (pick >= 0) break;
+    if (capturing_) return;  // a capture cannot be ordered after work outside it
+    bool any_busy = false;
+    for (uint32_t r = 0; r < kRegions; ++r) {
+      if (reg[r].in_graph) continue;
+      if (reg[r].busy) {
+        any_busy = true;
+        continue;
+      }
+      if (pick < 0 || reg[r].last_use < reg[pick].last_use) pick = (int)r;
     }
+    if (pick >= 0) {
+      // its last user was another stream (or this one's other region): wait for that use on the device
+      if (reg[pick].recorded && hipStreamWaitEvent(stream, reg[pick].done, 0) != hipSuccess) {
+        (void)hipGetLastError();
+        return;
+      }
+      break;
+    }
+    if (!any_busy) return;  // cannot happen: one region always stays outside graphs
+    ds.freed.wait(lock);    // every candidate is in another thread's hands for a few microseconds
+  }
+  if (capturing_ && !reg[pick].in_graph) {
+    // this use would tie the region to a graph: refuse if it is the last one outside graphs
+    uint32_t others_free = 0;
+    for (uint32_t r = 0; r < kRegions; ++r)
+      if ((int)r != pick && !reg[r].in_graph) ++others_free;
+    if (others_free == 0) return;
   }
   reg[pick].taken = true;
+  reg[pick].busy = true;
   reg[pick].owner = stream;
-  *out = &reg[pick];
-  return g_scratch.base[dev] + (uint64_t)pick * kRegionSlots;
-}
-
-// Caller holds g_scratch.mu; called after the last kernel of a call has been enqueued.
-void release_region(Region *r, hipStream_t stream) {
-  r->last_use = ++g_scratch.clock;
-  if (stream_is_capturing(stream)) {  // the graph's own ordering covers its replays on one stream
-    r->in_graph = true;
-    return;
-  }
-  if (!r->done && hipEventCreateWithFlags(&r->done, hipEventDisableTiming) != hipSuccess) {
-    (void)hipGetLastError();
-    r->done = nullptr;
-  }
-  r->recorded = r->done && hipEventRecord(r->done, stream) == hipSuccess;
-  if (!r->recorded) {
-    // no event to hand the region over with: leave it idle instead
-    (void)hipGetLastError();
-    (void)hipStreamSynchronize(stream);
+  dev_ = &ds;
+  region_ = &reg[pick];
+  slots_ = ds.base + (uint64_t)pick * kRegionSlots;
+  const int64_t now = g_leases.fetch_add(1, std::memory_order_relaxed) + 1;
+  int64_t seen = g_leases_max.load(std::memory_order_relaxed);
+  while (now > seen && !g_leases_max.compare_exchange_weak(seen, now, std::memory_order_relaxed)) {
   }
 }
 
-}  // namespace
-
-ScratchLease::ScratchLease(hipStream_t stream) : lock_(g_scratch.mu), stream_(stream) {
-  slots_ = acquire_region(stream, &region_);
-  if (!slots_) region_ = nullptr;
-}
-
+// Runs after the last kernel of the call has been enqueued.
 ScratchLease::~ScratchLease() {
-  if (region_) release_region(region_, stream_);
+  if (!region_) return;
+  Region *r = region_;
+  hipEvent_t ev = nullptr;
+  bool recorded = false;
+  if (!capturing_) {
+    // the event is only ever touched by the thread that holds the busy mark
+    ev = r->done;
+    if (!ev && hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) {
+      (void)hipGetLastError();
+      ev = nullptr;
+    }
+    recorded = ev && hipEventRecord(ev, stream_) == hipSuccess;
+    if (!recorded) {
+      // no event to hand the region over with: leave it idle instead
+      (void)hipGetLastError();
+      (void)hipStreamSynchronize(stream_);
+    }
+  }
+  {
+    std::lock_guard<std::mutex> lock(dev_->mu);
+    r->last_use = ++dev_->clock;
+    if (capturing_) {
+      r->in_graph = true;  // the graph's own ordering covers its replays on one stream
+    } else {
+      r->done = ev;
+      r->recorded = recorded;
+    }
+    r->busy = false;
+  }
+  g_leases.fetch_sub(1, std::memory_order_relaxed);
+  dev_->freed.notify_all();
+}
+
+int64_t scratch_max_concurrent(bool reset) {
+  return reset ? g_leases_max.exchange(0, std::memory_order_relaxed) : g_leases_max.load(std::memory_order_relaxed);
+}
+
+int scratch_release(hipStream_t stream) {
+  int dev = 0;
+  EW_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return EW_EINVAL;
+  DeviceScratch &ds = g_scratch[dev];
+  std::lock_guard<std::mutex> lock(ds.mu);
+  for (uint32_t r = 0; r < kRegions; ++r)
+    if (ds.region[r].taken && ds.region[r].owner == stream && !ds.region[r].busy) ds.region[r].in_graph = false;
+  return EW_OK;
 }
 
 bool tables_usable(const ew_plan_t *plan) {
@@ -240,6 +296,9 @@ int ew_set_param(const char *name, int64_t value) {
   } else if (!std::strcmp(name, "fused_wgs_per_cu")) {
     if (value < 0 || value > 8) return EW_EINVAL;
     k.fused_wgs_per_cu = value;
+  } else if (!std::strcmp(name, "fused_mode")) {
+    if (value < 0 || value > 1) return EW_EINVAL;
+    k.fused_mode = value;
   } else if (!std::strcmp(name, "verify_wgs_per_cu")) {
     if (value < 0 || value > 8) return EW_EINVAL;
     k.verify_wgs_per_cu = value;
@@ -249,6 +308,9 @@ int ew_set_param(const char *name, int64_t value) {
   } else if (!std::strcmp(name, "tile_align_bytes")) {
     if (value < 0 || value > 4096 || (value & (value - 1)) || (value && value < 16)) return EW_EINVAL;
     k.tile_align_bytes = value;
+  } else if (!std::strcmp(name, "scratch_max_concurrent")) {
+    if (value != 0) return EW_EINVAL;  // a statistic: it can only be reset
+    (void)ew::scratch_max_concurrent(true);
   } else {
     return EW_EINVAL;
   }
@@ -266,10 +328,14 @@ int64_t ew_get_param(const char *name) {
   if (!std::strcmp(name, "tile_bytes")) return k.tile_bytes;
   if (!std::strcmp(name, "tile_align_bytes")) return k.tile_align_bytes;
   if (!std::strcmp(name, "fused_wgs_per_cu")) return k.fused_wgs_per_cu;
+  if (!std::strcmp(name, "fused_mode")) return k.fused_mode;
   if (!std::strcmp(name, "verify_wgs_per_cu")) return k.verify_wgs_per_cu;
   if (!std::strcmp(name, "adam_wgs_per_cu")) return k.adam_wgs_per_cu;
+  if (!std::strcmp(name, "scratch_max_concurrent")) return ew::scratch_max_concurrent(false);
   return -1;
 }
+
+int ew_scratch_release(void *stream) { return ew::scratch_release((hipStream_t)stream); }
 
 int ew_single_bit_flip(const ew_cksum_t *diff, uint32_t *lane, int32_t *direction) {
   if (!diff || !lane || !direction) return 0;

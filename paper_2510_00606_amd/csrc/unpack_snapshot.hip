@@ -8,7 +8,9 @@
 // contributes  element << 8*(o mod 8)  to the record of block o >> 20.  Each workgroup writes its
 // tile's (sum, xor) to the tile's slot of a scratch region; the rare tile that straddles a block
 // boundary adds its upper part to the next block's record directly.  ew_fold_tiles_kernel then
-// walks the slots in tile order and adds runs of equal (rank, block) to the records.
+// walks the slots in tile order and adds runs of equal (rank, block) to the records.  When no
+// scratch region can be had (a stream under graph capture that would take the last region outside
+// graphs), every workgroup adds its tile to the record itself: same bits, more atomics.
 #include <cstring>
 #include <type_traits>
 
@@ -37,7 +39,7 @@ __device__ __forceinline__ void add_to_record(ew_cksum_t *rec, uint64_t sum, uin
   atomicXor(reinterpret_cast<unsigned long long *>(&rec->xr), (unsigned long long)xr);
 }
 
-template <int ES>
+template <int ES, bool SLOTS>
 __global__ __launch_bounds__(kThreads) void ew_unpack_snap_kernel(TableRef table, uint64_t tile_base, CopyTabs tabs,
                                                                   SnapTabs st, ew_cksum_t *__restrict__ slots) {
   __shared__ uint64_t lds_sum[kThreads / 64], lds_xor[kThreads / 64];
@@ -103,10 +105,14 @@ __global__ __launch_bounds__(kThreads) void ew_unpack_snap_kernel(TableRef table
   }
   block_fold(sum, xr, lds_sum, lds_xor);
   if (threadIdx.x == 0) {
-    ew_cksum_t r;
-    r.sum = sum;
-    r.xr = xr;
-    slots[blockIdx.x] = r;
+    if (SLOTS) {
+      ew_cksum_t r;
+      r.sum = sum;
+      r.xr = xr;
+      slots[blockIdx.x] = r;
+    } else {
+      add_to_record(st.rec[tl.dst_buf] + (dbyte >> 20), sum, xr);
+    }
   }
   if (straddle) {
     block_fold(sum_hi, xr_hi, lds_sum_hi, lds_xor_hi);
@@ -163,8 +169,14 @@ int launch_pass(const ew::TileTable &tt, uint64_t t0, uint64_t n, const CopyTabs
   // buffers, 6.04 -> 6.09 in a fast one; five per CU gains more in the slow case and loses in the
   // fast one, four loses in both).  The cap is set by asking for unused dynamic LDS.
   const uint32_t lds_pad = ew::occupancy_pad(ew::knobs().fused_wgs_per_cu, 8 * sizeof(uint64_t) * (kThreads / 64));
-  hipLaunchKernelGGL(ew_unpack_snap_kernel<ES>, dim3((uint32_t)n), dim3(kThreads), lds_pad, stream, tt.dev, t0, tabs,
-                     st, slots);
+  if (!slots) {  // no scratch region: the workgroups add to the records themselves
+    hipLaunchKernelGGL((ew_unpack_snap_kernel<ES, false>), dim3((uint32_t)n), dim3(kThreads), lds_pad, stream, tt.dev,
+                       t0, tabs, st, slots);
+    EW_HIP(hipGetLastError());
+    return EW_OK;
+  }
+  hipLaunchKernelGGL((ew_unpack_snap_kernel<ES, true>), dim3((uint32_t)n), dim3(kThreads), lds_pad, stream, tt.dev, t0,
+                     tabs, st, slots);
   EW_HIP(hipGetLastError());
   hipLaunchKernelGGL(ew_fold_tiles_kernel<ES>, dim3((uint32_t)fold_grid), dim3(kThreads), 0, stream, tt.dev, t0, n,
                      kTilesPerLane, st, slots);
@@ -203,13 +215,14 @@ int unpack_snapshot(const ew_plan_t *plan, int which, const void *stage, const v
     if (st.nblk[k] > max_blk) max_blk = st.nblk[k];
   }
   ew::ScratchLease lease(stream);
-  ew_cksum_t *slots = lease.slots();
-  if (!slots) return EW_ENOMEM;  // only for a capturing stream that owns no region
+  ew_cksum_t *slots = lease.slots();  // nullptr: launch_pass takes the scratch-free form
+  if (ew::knobs().fused_mode == 1) slots = nullptr;
   hipLaunchKernelGGL(ew_zero_records_kernel, dim3((2 * max_blk + kThreads - 1) / kThreads, plan->new_dp),
                      dim3(kThreads), 0, stream, st);
   EW_HIP(hipGetLastError());
-  for (uint64_t t0 = 0; t0 < tt.ntiles; t0 += ew::kRegionSlots) {
-    const uint64_t n = tt.ntiles - t0 < ew::kRegionSlots ? tt.ntiles - t0 : ew::kRegionSlots;
+  const uint64_t per_pass = slots ? ew::kRegionSlots : 0x7fffffffull;
+  for (uint64_t t0 = 0; t0 < tt.ntiles; t0 += per_pass) {
+    const uint64_t n = tt.ntiles - t0 < per_pass ? tt.ntiles - t0 : per_pass;
     const int prc = elem_size == 2 ? launch_pass<2>(tt, t0, n, tabs, st, slots, stream)
                                    : launch_pass<4>(tt, t0, n, tabs, st, slots, stream);
     if (prc != EW_OK) return prc;

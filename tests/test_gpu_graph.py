@@ -71,3 +71,76 @@ def test_step_replays_from_a_hip_graph():
         # and the eager result is not trivially zero
         assert int(e_buf["nsums"]["W"][0][:, 0].abs().sum().item()) != 0
     plan.close()
+
+
+def test_four_capturing_streams_leave_eager_calls_working():
+    """Four streams of one device each capture a fused unpack + snapshot.  Three of the captures tie a
+    scratch region to their graph; the fourth would take the last region outside graphs, so it records
+    the scratch-free kernels instead.  An eager call on a fifth stream still gets a region, every
+    replay equals the eager result, and ew_scratch_release gives the regions back afterwards."""
+    Do, Dn, mask, N, C, es = 5, 4, 0b11011, 700_000, 40_000, 4
+    plan = ew.ew_plan(Do, Dn, mask, N, C)
+    ew.ew_plan_upload(plan, 0, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    alive = [(mask >> j) & 1 for j in range(Do)]
+    old_len = [plan.old_shard_len(j) for j in range(Do)]
+
+    def buffers(seed):
+        old = [synth.fill(seed, j, "W", 0, old_len[j], DEV) for j in range(Do)]
+        live = [t if alive[j] else None for j, t in enumerate(old)]
+        snaps = [None if alive[j] else t for j, t in enumerate(old)]
+        stage = torch.zeros(plan.stage_len, dtype=torch.float32, device=DEV)
+        new = [torch.zeros(plan.new_shard_len(k), dtype=torch.float32, device=DEV) for k in range(Dn)]
+        nsn = [torch.zeros_like(t) for t in new]
+        ck = [torch.zeros((ew.num_blocks(t.numel() * es), 2), dtype=torch.int64, device=DEV) for t in new]
+        return live, snaps, stage, new, nsn, ck
+
+    def enqueue(b, st):
+        live, snaps, stage, new, nsn, ck = b
+        ew.ew_pack(plan, live, snaps, stage, es, st)
+        ew.ew_unpack_snapshot(plan, stage, live, snaps, new, nsn, ck, es, st)
+        ew.ew_snapshot(new[0], nsn[0], new[0].numel() * es, ck[0], st)
+
+    streams = [torch.cuda.Stream() for _ in range(4)]
+    bufs = [buffers(40 + i) for i in range(4)]
+    for s, b in zip(streams, bufs):           # warm-up: every stream claims a region
+        with torch.cuda.stream(s):
+            enqueue(b, s.cuda_stream)
+    torch.cuda.synchronize()
+    graphs = []
+    for s, b in zip(streams, bufs):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            enqueue(b, torch.cuda.current_stream().cuda_stream)
+        graphs.append(g)
+    # eager work on a stream that owns nothing: must still find a region (and give the right bits)
+    eager = [buffers(40 + i) for i in range(4)]
+    for rep in range(3):
+        for b in bufs:
+            for t in b[3] + b[4]:
+                t.zero_()
+            for c in b[5]:
+                c.fill_(-1)
+        torch.cuda.synchronize()
+        for g in graphs:
+            g.replay()
+        for b in eager:
+            enqueue(b, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        for i, (b, e) in enumerate(zip(bufs, eager)):
+            for key in (3, 4, 5):
+                for x, y in zip(b[key], e[key]):
+                    assert torch.equal(x.view(torch.uint8), y.view(torch.uint8)), f"replay {rep}, graph {i}, buffer {key}"
+        assert int(eager[0][5][0][:, 0].abs().sum().item()) != 0
+    del graphs
+    torch.cuda.synchronize()
+    for s in streams:
+        ew.ew_scratch_release(s.cuda_stream)
+    for s, b in zip(streams, bufs):           # and after the release everything still works
+        with torch.cuda.stream(s):
+            enqueue(b, s.cuda_stream)
+    torch.cuda.synchronize()
+    for b, e in zip(bufs, eager):
+        for x, y in zip(b[5], e[5]):
+            assert torch.equal(x, y)
+    plan.close()

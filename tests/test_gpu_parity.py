@@ -17,7 +17,8 @@ MIB = 1 << 20
 @pytest.fixture(autouse=True)
 def default_params():
     saved = {k: ew.ew_get_param(k) for k in ("tile_bytes", "tile_elems", "tile_align_bytes", "cksum_sub_bytes", "cksum_wgs_per_cu",
-                                              "cksum_mode", "fused_wgs_per_cu", "verify_wgs_per_cu", "snapshot_wave_min_bytes")}
+                                              "cksum_mode", "fused_wgs_per_cu", "fused_mode", "verify_wgs_per_cu",
+                                              "snapshot_wave_min_bytes")}
     yield
     for k, v in saved.items():
         ew.ew_set_param(k, v)
@@ -328,6 +329,18 @@ def test_fused_unpack_with_occupancy_caps(wgs):
         reshard_case(3, 2, 0b111, 2_600_000, 99_992, es, rng)
 
 
+def test_fused_unpack_scratch_free_form():
+    """The form a graph capture falls back to when it can get no scratch region: every workgroup adds
+    its tile to the records with atomics.  Same bits as the slot form and as the oracle."""
+    ew.ew_set_param("fused_mode", 1)
+    rng = np.random.default_rng(321)
+    for es in (2, 4):
+        reshard_case(8, 7, 0xFF & ~(1 << 5), 3_000_000 + 8 * 37, 262144, es, rng)
+        reshard_case(3, 2, 0b111, 2_600_000, 99_992, es, rng)      # tiles straddling checksum blocks
+        reshard_case(2, 3, 0b10, 1_900_003, 70_001, es, rng)       # ragged units: words split between segments
+        reshard_case(4, 3, 0b1011, 4099, 264, es, rng)
+
+
 def test_null_buffers_are_rejected():
     plan = ew.ew_plan(4, 3, 0b1011, 1 << 16, 4096)
     ew.ew_plan_upload(plan, 0, stream())
@@ -433,6 +446,97 @@ def test_snapshot_from_several_host_threads():
     for i in range(n_threads):
         assert np.array_equal(dst[i].cpu().numpy(), raw[i])
         assert np.array_equal(ck[i].cpu().numpy().view(np.uint64), checksum.block_checksums(raw[i]))
+
+
+def test_two_host_threads_share_one_stream():
+    """Two host threads issue snapshots on the SAME stream at the same time.  Their (slot kernel, fold
+    kernel) pairs may interleave on the stream, so each call holds a scratch region of its own while it
+    enqueues; every result is the oracle's."""
+    import threading
+    rng = np.random.default_rng(80)
+    n_threads, reps = 2, 40
+    nbytes = [3 * MIB + 4096 + 9, 2 * MIB + 8192 + 3]
+    raw = [[rng.integers(0, 256, nbytes[i], dtype=np.uint8) for _ in range(3)] for i in range(n_threads)]
+    src = [[torch.from_numpy(r).to(DEV) for r in rs] for rs in raw]
+    dst = [[torch.zeros(nbytes[i], dtype=torch.uint8, device=DEV) for _ in range(3)] for i in range(n_threads)]
+    ck = [[torch.zeros((ew.num_blocks(nbytes[i]), 2), dtype=torch.int64, device=DEV) for _ in range(3)]
+          for i in range(n_threads)]
+    shared = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    errors = []
+    go = threading.Barrier(n_threads)
+
+    def work(i):
+        try:
+            go.wait()
+            for r in range(reps):
+                b = r % 3
+                ew.ew_snapshot(src[i][b], dst[i][b], nbytes[i], ck[i][b], shared.cuda_stream)
+        except Exception as e:   # reported by the main thread
+            errors.append((i, repr(e)))
+
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(n_threads)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for i in range(n_threads):
+        for b in range(3):
+            assert np.array_equal(dst[i][b].cpu().numpy(), raw[i][b])
+            assert np.array_equal(ck[i][b].cpu().numpy().view(np.uint64), checksum.block_checksums(raw[i][b]))
+
+
+def test_enqueues_on_two_streams_overlap():
+    """The scratch lock is held only while a region is picked and while its event is recorded, so two
+    host threads on two streams are inside the library's enqueue section at the same time: the
+    library's own count of regions held at once reaches two (tried a few times: whether the two
+    threads meet in a given round is up to the scheduler), and the results are the oracle's."""
+    import threading
+    rng = np.random.default_rng(81)
+    nbytes = 5 * (1 << 30) // 2 + 4096 + 5     # 2.5 GiB: two passes over a region per call
+    raw8 = rng.integers(0, 1 << 62, 1 << 16, dtype=np.int64)
+    src = torch.from_numpy(raw8).to(DEV).repeat((nbytes + 8 * len(raw8) - 1) // (8 * len(raw8))).view(torch.uint8)[:nbytes]
+    dst = [torch.zeros(nbytes, dtype=torch.uint8, device=DEV) for _ in range(2)]
+    ck = [torch.zeros((ew.num_blocks(nbytes), 2), dtype=torch.int64, device=DEV) for _ in range(2)]
+    streams = [torch.cuda.Stream() for _ in range(2)]
+    torch.cuda.synchronize()
+    errors = []
+    seen = 0
+    for attempt in range(5):
+        ew.ew_set_param("scratch_max_concurrent", 0)
+        go = threading.Barrier(2)
+
+        def work(i):
+            try:
+                go.wait()
+                for _ in range(60):
+                    ew.ew_snapshot(src, dst[i], nbytes, ck[i], streams[i].cuda_stream)
+            except Exception as e:   # reported by the main thread
+                errors.append((i, repr(e)))
+
+        threads = [threading.Thread(target=work, args=(i,)) for i in range(2)]
+        for t in threads:
+            t.start()
+        for t in threads:
+            t.join()
+        torch.cuda.synchronize()
+        assert not errors, errors
+        seen = ew.ew_get_param("scratch_max_concurrent")
+        if seen >= 2:
+            break
+    assert seen >= 2, "two streams' enqueues never overlapped"
+    want = None
+    for i in range(2):
+        assert torch.equal(dst[i], src)
+        got = ck[i].cpu().numpy().view(np.uint64)
+        if want is None:   # oracle on sampled blocks (both ends, both sides of the pass boundary), then equality
+            for b in (0, 1, 2047, 2048, 2049, len(got) - 2, len(got) - 1):
+                host = src[b * MIB:min((b + 1) * MIB, nbytes)].cpu().numpy()
+                assert np.array_equal(got[b], checksum.block_checksums(host)[0]), f"block {b}"
+            want = got
+        assert np.array_equal(got, want)
 
 
 @pytest.mark.timeout(600)
