@@ -47,7 +47,8 @@ enum {
   EW_EUNRECOVERABLE = -2,  /* no survivor, or a failed rank whose ring predecessor failed too */
   EW_ENOMEM = -3,          /* host or device allocation failed                                 */
   EW_EHIP = -4,            /* HIP runtime error; text of the last one via ew_strerror(EW_EHIP) */
-  EW_EINFEASIBLE = -5      /* ew_partition_layers: no partition fits the stages' memory caps   */
+  EW_EINFEASIBLE = -5,     /* ew_partition_layers: no partition fits the stages' memory caps   */
+  EW_ETOOBIG = -6          /* ew_snapshot_noalloc: nbytes above EW_NOALLOC_MAX_BYTES           */
 };
 
 typedef struct ew_plan_s ew_plan_t; /* opaque */
@@ -254,6 +255,20 @@ int ew_snapshot(const void *src, void *dst, uint64_t nbytes, ew_cksum_t *cksums,
  * destroyed and its replays are complete: the scratch regions those graphs used may change hands
  * again.  Harmless when there is nothing to release. */
 int ew_scratch_release(void *stream);
+
+/* ---- ew_snapshot for callers that cannot allocate ----------------------------------------------
+ * For code under HIP graph capture, tight serving loops and harnesses that forbid allocation: same
+ * arguments and results as ew_snapshot, but the call touches no allocator of any kind -- no
+ * hipMalloc / hipFree, no event or lock creation, no scratch lease.  Its checksum slots live in a
+ * second fixed device array of 16 MiB (one 16-byte slot per KiB of input) that every GPU the
+ * library runs on holds until the process ends; the array's address is looked up on the first call
+ * on each device (make that call outside a capture).
+ * nbytes above EW_NOALLOC_MAX_BYTES (1 GiB: more than one fp32 array of a 7B-stage rank shard)
+ * returns EW_ETOOBIG and does nothing.  All calls on one GPU share the array: calls that may run at
+ * the same time on one GPU (different streams) race on it and must be serialised by the caller;
+ * calls on one stream are safe back to back.  Nothing in the array needs clearing between calls. */
+#define EW_NOALLOC_MAX_BYTES ((uint64_t)1 << 30)
+int ew_snapshot_noalloc(const void *src, void *dst, uint64_t nbytes, ew_cksum_t *cksums, void *stream);
 
 /* ---- Integrity check of stored bytes (Live Remap step 1) ----------------------------------
  * Recomputes the block checksums of buf into got[] (device, ceil(nbytes/2^20) records,

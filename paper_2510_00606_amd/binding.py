@@ -13,7 +13,8 @@ import os
 
 import numpy as np
 
-EW_OK, EW_EINVAL, EW_EUNRECOVERABLE, EW_ENOMEM, EW_EHIP, EW_EINFEASIBLE = 0, -1, -2, -3, -4, -5
+EW_OK, EW_EINVAL, EW_EUNRECOVERABLE, EW_ENOMEM, EW_EHIP, EW_EINFEASIBLE, EW_ETOOBIG = 0, -1, -2, -3, -4, -5, -6
+EW_NOALLOC_MAX_BYTES = 1 << 30
 EW_MAX_DP = 64
 EW_GRANULE = 8
 EW_CKSUM_BLOCK = 1 << 20
@@ -71,6 +72,7 @@ _SIGNATURES = {
     "ew_reshard_snapshot": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32,
                                       C.c_void_p]),
     "ew_snapshot": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]),
+    "ew_snapshot_noalloc": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]),
     "ew_scratch_release": (C.c_int, [C.c_void_p]),
     "ew_verify": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                             C.c_uint64, C.c_void_p]),
@@ -364,6 +366,15 @@ def ew_snapshot(src, dst, nbytes: int, cksums, stream=None):
         if n is not None and n < need:
             raise ValueError(f"{name} holds {n} bytes, call needs {need}")
     _check(lib().ew_snapshot(_ptr(src), _ptr(dst), nbytes, _ptr(cksums), _stream(stream)), "ew_snapshot")
+
+
+def ew_snapshot_noalloc(src, dst, nbytes: int, cksums, stream=None):
+    for name, b, need in (("src", src, nbytes), ("dst", dst, nbytes), ("cksums", cksums, 16 * num_blocks(nbytes))):
+        n = _nbytes(b)
+        if n is not None and n < need:
+            raise ValueError(f"{name} holds {n} bytes, call needs {need}")
+    _check(lib().ew_snapshot_noalloc(_ptr(src), _ptr(dst), nbytes, _ptr(cksums), _stream(stream)),
+           "ew_snapshot_noalloc")
 
 
 def ew_scratch_release(stream=None):

@@ -3,6 +3,8 @@
 // changed.  A block is EW_CKSUM_BLOCK = 1 MiB; its record is the wrapping sum and the xor of its
 // little-endian 64-bit words, the last word zero-padded.  Both operations commute, so the bits do
 // not depend on the order in which partial results meet.  HBM-bandwidth bound, no MFMA.
+#include <atomic>
+
 #include "device_util.h"
 #include "runtime.h"
 
@@ -287,9 +289,49 @@ int launch_cksum(const void *src, void *dst, uint64_t nbytes, ew_cksum_t *out, h
   return launch_cksum_slots<COPY>(src, dst, nbytes, out, slots, ew::kRegionSlots, stream);
 }
 
+// ---- the allocation-free entry point's own scratch ----------------------------------------------
+// A fixed array of checksum slots for ew_snapshot_noalloc, apart from the leased regions above: no
+// lease, no event, no lock.  In host code the array's name only stands for the symbol; the memory is
+// reached through the per-device address that hipGetSymbolAddress returned for it.
+constexpr uint64_t kNoAllocSlots = EW_NOALLOC_MAX_BYTES / 1024;  // one slot per KiB: 16 MiB of slots
+static __device__ __align__(256) ew_cksum_t scratch[kNoAllocSlots];
+constexpr int kNoAllocMaxDevices = 64;
+std::atomic<ew_cksum_t *> g_noalloc_ptr[kNoAllocMaxDevices];  // zero-initialised; a race only repeats the query
+
+// Address of the current device's copy of `scratch`, looked up on the first call on that device.
+int noalloc_scratch(ew_cksum_t **out) {
+  int dev = -1;
+  EW_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kNoAllocMaxDevices) return EW_EINVAL;
+  ew_cksum_t *p = g_noalloc_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    void *q = nullptr;
+    EW_HIP(hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)));
+    if (!q) return ew::hip_fail(hipErrorInvalidSymbol, "hipGetSymbolAddress(scratch) returned no address");
+    p = (ew_cksum_t *)q;
+    g_noalloc_ptr[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return EW_OK;
+}
+
 }  // namespace
 
 extern "C" {
+
+int ew_snapshot_noalloc(const void *src, void *dst, uint64_t nbytes, ew_cksum_t *cksums, void *stream) {
+  if (nbytes == 0) return EW_OK;
+  if (!src || !dst || !cksums) return EW_EINVAL;
+  if (nbytes > EW_NOALLOC_MAX_BYTES) return EW_ETOOBIG;
+  if ((((uintptr_t)src | (uintptr_t)dst) & 15u) != 0)  // the streaming kernel needs no scratch at all
+    return launch_cksum_streaming<true>(src, dst, nbytes, cksums, (hipStream_t)stream);
+  ew_cksum_t *slots = nullptr;
+  const int rc = noalloc_scratch(&slots);
+  if (rc != EW_OK) return rc;
+  // Every slot the fold kernel reads was written by this call's slot kernel, so what earlier calls
+  // left in the array never needs clearing.
+  return launch_cksum_slots<true>(src, dst, nbytes, cksums, slots, kNoAllocSlots, (hipStream_t)stream);
+}
 
 int ew_snapshot(const void *src, void *dst, uint64_t nbytes, ew_cksum_t *cksums, void *stream) {
   if (nbytes == 0) return EW_OK;

@@ -362,6 +362,9 @@ const char *ew_strerror(int code) {
     case EW_ENOMEM: return "out of memory";
     case EW_EHIP: return ew::last_hip_error();
     case EW_EINFEASIBLE: return "infeasible: no layer partition fits the stages' memory caps";
+    case EW_ETOOBIG:
+      return "too big: the input exceeds the fixed scratch array of the allocation-free entry point "
+             "(EW_NOALLOC_MAX_BYTES per call)";
     default: return "unknown error code";
   }
 }

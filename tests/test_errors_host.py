@@ -28,6 +28,14 @@ def test_hip_failure_text_reaches_strerror():
 
 def test_argument_checks_come_before_any_hip_call():
     a = np.zeros(64, np.uint8)
+    for call in (lambda: ew.ew_snapshot_noalloc(a.ctypes.data, a.ctypes.data + 32, ew.EW_NOALLOC_MAX_BYTES + 1, a.ctypes.data, None),):
+        with pytest.raises(ew.EwError) as e:
+            call()
+        assert e.value.code == ew.EW_ETOOBIG and "too big" in ew.ew_strerror(ew.EW_ETOOBIG)
+    with pytest.raises(ew.EwError) as e:
+        ew.ew_snapshot_noalloc(None, a.ctypes.data, 16, a.ctypes.data, None)
+    assert e.value.code == ew.EW_EINVAL
+    ew.ew_snapshot_noalloc(None, None, 0, None, None)      # zero bytes: nothing to do, no error
     with pytest.raises(ew.EwError) as e:
         ew.ew_memcpy(a.ctypes.data, a.ctypes.data + 32, 24, None)
     assert e.value.code == ew.EW_EINVAL
