@@ -15,6 +15,11 @@ one state array at a time (that array resident before its own timed steps) and t
 time; `ms_per_step` is the figure that shows what fusing a6 and a7 saves.  The path not chosen for
 the headline is timed too, after the timed region, and reported under "other_path".
 
+After the timed region the default run (7b_stage) also measures, each on its own and briefly, the
+other named workloads -- tiny (latencies), one 7B rank shard's snapshot + verify, the 13B stage and
+the 70B stage -- and reports them under "workloads" (--no-workloads skips this).  The CPU baseline
+is the oracle alone: nothing of the library is called inside it.
+
 Prints ONE JSON line.  --gpus above 1 is refused: this build is one GPU only.
 """
 from __future__ import annotations
@@ -43,7 +48,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="7b_stage", choices=["tiny", "7b_stage", "13b_stage", "70b_stage"],
+    ap.add_argument("--workload", default="7b_stage",
+                    choices=["tiny", "7b_stage", "7b_rank_snapshot", "13b_stage", "70b_stage"],
                     help="70b_stage does not fit 288 GB with all four arrays resident: it is measured one "
                          "array at a time (each array resident before its own timed steps) and summed")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -52,6 +58,8 @@ def parse():
                     help="headline path runs a6 (ew_unpack) and a7 (ew_snapshot) separately")
     ap.add_argument("--no-other-path", action="store_true", help="do not time the path that is not the headline")
     ap.add_argument("--no-migration", action="store_true", help="skip the layer-migration comparison (Sec. 6.3)")
+    ap.add_argument("--no-workloads", action="store_true",
+                    help="skip the brief measurements of the other named workloads after the timed region")
     ap.add_argument("--no-grad-snapshot", action="store_true",
                     help="skip the gradient-shipping snapshot measurement (Sec. 5.1)")
     return ap.parse_args()
@@ -75,10 +83,11 @@ def read_traffic(kernel_key):
 
 def merge_paths(parts):
     """Sums the per-array measurements of one path."""
-    out = {"ms_per_step": 0.0, "plan_ms": 0.0, "phase_ms": {}, "phase_median_ms": {}, "bytes_phase": {}, "launches": {}}
+    out = {"ms_per_step": 0.0, "plan_ms": 0.0, "step_device_ms_min": 0.0, "step_device_ms_max": 0.0,
+           "phase_ms": {}, "phase_median_ms": {}, "bytes_phase": {}, "launches": {}}
     for p in parts:
-        out["ms_per_step"] += p["ms_per_step"]
-        out["plan_ms"] += p["plan_ms"]
+        for key in ("ms_per_step", "plan_ms", "step_device_ms_min", "step_device_ms_max"):
+            out[key] += p[key]
         for key in ("phase_ms", "phase_median_ms", "bytes_phase", "launches"):
             for ph, v in p[key].items():
                 out[key][ph] = out[key].get(ph, 0) + v
@@ -110,10 +119,11 @@ def summarise(path, workload_name):
                 "bytes_per_launch": round(d_bytes / d_launches), "avg_launch_us": round(d_ms / d_launches * 1e3, 2)}
     step_bytes = sum(bytes_phase.values())
     return {"ms_per_step": path["ms_per_step"], "value": step_bytes / path["ms_per_step"] / 1e6,
+            "step_device_ms_min": path["step_device_ms_min"], "step_device_ms_max": path["step_device_ms_max"],
             "step_GB": step_bytes / 1e9, "plan_ms": path["plan_ms"], "kernels": kernels, "roofline": roofline}
 
 
-def measure(args, ew, synth, torch, w, starts, A, keep_state):
+def measure(args, ew, synth, torch, w, starts, A, keep_state, steps=None, warmup=None, do_other=None, extras=True):
     """Everything that needs the state arrays `A` of workload `w` resident in HBM: the timed steps of
     the headline path, the other path, the plain-copy yardstick and the stand-alone reshard time."""
     dev = "cuda:0"
@@ -121,6 +131,9 @@ def measure(args, ew, synth, torch, w, starts, A, keep_state):
     bpe = sum(synth.ELEM_SIZE[a] for a in A)
     es = synth.ELEM_SIZE
     numel = w.numel
+    steps = args.steps if steps is None else steps
+    warmup = args.warmup if warmup is None else warmup
+    do_other = (not args.no_other_path) if do_other is None else do_other
     # ---------------- setup (untimed): state resident in HBM
     plan0 = ew.ew_plan_bounds(w.old_dp, w.new_dp, w.alive_mask, starts)
     alive = [(w.alive_mask >> j) & 1 for j in range(w.old_dp)]
@@ -225,12 +238,14 @@ def measure(args, ew, synth, torch, w, starts, A, keep_state):
         phase_ms = {ph: sum(ev[i].elapsed_time(ev[i + 1]) for _, ev in records) / steps for i, ph in enumerate(phases)}
         phase_median = {ph: sorted(ev[i].elapsed_time(ev[i + 1]) for _, ev in records)[steps // 2]
                         for i, ph in enumerate(phases)}
+        per_step = [ev[0].elapsed_time(ev[-1]) for _, ev in records]   # device time of each step, plan excluded
         return {"ms_per_step": elapsed / steps * 1e3, "plan_ms": sum(r[0] for r in records) / steps * 1e3,
+                "step_device_ms_min": min(per_step), "step_device_ms_max": max(per_step),
                 "phase_ms": phase_ms, "phase_median_ms": phase_median, "bytes_phase": bytes_phase, "launches": launches}
 
     # ---------------- the timed region (inside run_path): exactly K steps of the headline path
-    head = run_path(args.unfused, args.steps, args.warmup)
-    other = None if args.no_other_path else run_path(not args.unfused, args.steps, 1)
+    head = run_path(args.unfused, steps, warmup)
+    other = run_path(not args.unfused, steps, 1) if do_other else None
 
     # yardstick (outside the timed region): the library's plain copy kernel on one fp32 rank shard,
     # i.e. what a copy with nothing else to do reaches on this GPU; these launches are also the
@@ -251,7 +266,7 @@ def measure(args, ew, synth, torch, w, starts, A, keep_state):
     # time to reshard one stage on its own (outside the timed region): plan + table upload + pack +
     # unpack of all four arrays, host clock around a synchronised run, median of 7
     reshard_runs = []
-    for _ in range(7):
+    for _ in range(7 if extras else 3):
         torch.cuda.synchronize()
         r0 = time.perf_counter()
         rp = ew.ew_plan_bounds(w.old_dp, w.new_dp, w.alive_mask, starts)
@@ -268,7 +283,7 @@ def measure(args, ew, synth, torch, w, starts, A, keep_state):
     # the same without the arena (holders and destinations in one address space, as on this one GPU):
     # plan + upload + ew_reshard of the four arrays, and the variant that also takes the new snapshot
     direct_runs, direct_snap_runs = [], []
-    for _ in range(7):
+    for _ in range(7 if extras else 3):
         for runs, with_snapshot in ((direct_runs, False), (direct_snap_runs, True)):
             torch.cuda.synchronize()
             r0 = time.perf_counter()
@@ -327,6 +342,160 @@ def measure(args, ew, synth, torch, w, starts, A, keep_state):
             "old_len": old_len, "keep": (old, alive) if keep_state else None, "tiny_latency": tiny_latency}
 
 
+def run_stage(args, ew, configs, synth, torch, name, steps=None, warmup=None, do_other=None, extras=True):
+    """Measures one of the stage workloads (tiny, 7b, 13b, 70b) and returns the summarised paths plus
+    what the callers report next to them."""
+    w = configs.ALL[name]()
+    starts = w.unit_starts()
+    A = list(synth.ARRAYS)
+    # all four arrays resident at once, except where that exceeds the GPU's memory
+    residency = [[a] for a in A] if w.name == "70b_stage" else [A]
+    parts = []
+    for group in residency:
+        parts.append(measure(args, ew, synth, torch, w, starts, group, keep_state=(len(residency) == 1),
+                             steps=steps, warmup=warmup, do_other=do_other, extras=extras))
+        torch.cuda.empty_cache()
+    res = {"w": w, "starts": starts,
+           "head": summarise(merge_paths([p["head"] for p in parts]), w.name),
+           "other": None if parts[0]["other"] is None else summarise(merge_paths([p["other"] for p in parts]), w.name),
+           "copy_gbs": parts[-1]["copy_gbs"],
+           "reshard_only_ms": sum(p["reshard_only_ms"] for p in parts),
+           "direct_ms": sum(p["direct_ms"] for p in parts),
+           "direct_snap_ms": sum(p["direct_snap_ms"] for p in parts),
+           "n_remote": parts[0]["n_remote"], "old_len": parts[0]["old_len"],
+           "keep": parts[0]["keep"], "tiny_latency": parts[0]["tiny_latency"]}
+    return res
+
+
+def rank_snapshot_measure(ew, configs, synth, torch, steps, warmup):
+    """The snapshot-only workload on its own: one 7B-stage rank shard (four arrays, 3.06 GB) copied with
+    per-MiB checksums (ew_snapshot), then verified (ew_verify).  One step = both, all four arrays."""
+    w = configs.snapshot_7b()
+    dev = "cuda:0"
+    st = torch.cuda.current_stream().cuda_stream
+    A, es = list(synth.ARRAYS), synth.ELEM_SIZE
+    src = {a: synth.fill(w.seed, 0, a, 0, w.numel, dev) for a in A}
+    dst = {a: torch.empty_like(src[a]) for a in A}
+    ck = {a: torch.zeros((ew.num_blocks(w.numel * es[a]), 2), dtype=torch.int64, device=dev) for a in A}
+    got = {a: torch.zeros_like(ck[a]) for a in A}
+    n_bad = torch.zeros(1, dtype=torch.int64, device=dev)
+    bad = torch.zeros(16, dtype=torch.int64, device=dev)
+    diffs = torch.zeros((16, 2), dtype=torch.int64, device=dev)
+    nbytes = sum(w.numel * es[a] for a in A)
+    rec = []
+
+    def step(record):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)] if record else None
+        if record:
+            ev[0].record()
+        for a in A:
+            ew.ew_snapshot(src[a], dst[a], w.numel * es[a], ck[a], st)
+        if record:
+            ev[1].record()
+        for a in A:
+            ew.ew_verify(dst[a], w.numel * es[a], ck[a], got[a], n_bad, bad, diffs, 16, st)
+        if record:
+            ev[2].record()
+            rec.append(ev)
+
+    for _ in range(warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step(True)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / steps * 1e3
+    assert int(n_bad.item()) == 0
+    snap_ms = sum(e[0].elapsed_time(e[1]) for e in rec) / steps
+    ver_ms = sum(e[1].elapsed_time(e[2]) for e in rec) / steps
+    ck_bytes = 16 * sum(int(ck[a].shape[0]) for a in A)
+    return {"w": w, "ms_per_step": ms, "step_bytes": 3 * nbytes + ck_bytes,
+            "kernels": {"snapshot": {"ms": round(snap_ms, 4), "launches": 4, "GB": round((2 * nbytes + ck_bytes) / 1e9, 4),
+                                     "GB/s": round((2 * nbytes + ck_bytes) / snap_ms / 1e6, 1),
+                                     "frac_of_peak": round((2 * nbytes + ck_bytes) / snap_ms / 1e6 / HBM_PEAK_GBS, 4)},
+                        "verify": {"ms": round(ver_ms, 4), "launches": 4, "GB": round(nbytes / 1e9, 4),
+                                   "GB/s": round(nbytes / ver_ms / 1e6, 1),
+                                   "frac_of_peak": round(nbytes / ver_ms / 1e6 / HBM_PEAK_GBS, 4)}}}
+
+
+def compact(res):
+    """What the "workloads" block keeps of one stage workload."""
+    h, w = res["head"], res["w"]
+    out = {"note": w.note, "state_GB": round(14 * w.numel / 1e9, 3), "remote_fraction": round(res["n_remote"] / w.numel, 4),
+           "ms_per_step": round(h["ms_per_step"], 3), "GBps": round(h["value"], 1),
+           "frac_of_hbm_peak": round(h["value"] / HBM_PEAK_GBS, 4), "plan_ms": round(h["plan_ms"], 3),
+           "reshard_one_stage_ms": round(res["reshard_only_ms"], 3),
+           "reshard_without_arena_ms": round(res["direct_ms"], 3),
+           "kernel_GBps": {ph: k["GB/s"] for ph, k in h["kernels"].items()},
+           "dominant_kernel": {"kernel": h["roofline"]["kernel"].split()[0], "GBps": h["roofline"]["achieved"],
+                               "frac": h["roofline"]["frac"], "avg_launch_us": h["roofline"]["avg_launch_us"]}}
+    if w.name == "70b_stage":
+        out["residency"] = "one state array at a time (299 GB do not fit 288 GB); the four are summed"
+    return out
+
+
+def oracle_remote_elems(o_lay, starts, old_dp, new_dp, alive_mask):
+    """Elements that change rank (the arena's length), from the oracle's layout functions alone."""
+    import numpy as np
+    alive = o_lay.alive_list(old_dp, alive_mask)
+    nro = o_lay.new_rank_of(old_dp, new_dp, alive)
+    lens, counts = np.unique(np.diff(np.asarray(starts, dtype=np.int64)), return_counts=True)
+    total = 0
+    for L, c in zip(lens.tolist(), counts.tolist()):
+        nb = o_lay.piece_bounds(L, new_dp)
+        per_unit = 0
+        for h in range(old_dp):
+            for lo, hi, _owner in o_lay.held_ranges(L, h, old_dp, alive):
+                for k in range(new_dp):
+                    if nro[h] != k:
+                        per_unit += max(0, min(hi, nb[k + 1]) - max(lo, nb[k]))
+        total += per_unit * c
+    return total
+
+
+def cpu_baseline(w, starts, host, n_units, threads):
+    """One pass of the hot path by the CPU oracle over the first n_units units: snapshot + checksum of
+    every old partition, verify of the failed ranks' snapshots, reconstruct + slice, snapshot +
+    checksum of the result.  Nothing of the library is called.  threads > 1 runs the state arrays side
+    by side (numpy releases the interpreter lock in its copies and reductions)."""
+    import numpy as np
+    from concurrent.futures import ThreadPoolExecutor
+    from oracle import checksum as o_ck
+    from oracle import layout as o_lay
+    s_starts = np.asarray(starts[:n_units + 1], dtype=np.int64)
+    al = o_lay.alive_list(w.old_dp, w.alive_mask)
+
+    def one_array(a):
+        n = 0
+        snaps_h = [h.copy() for h in host[a]]                         # a2: copy ...
+        cks = [o_ck.block_checksums(h) for h in snaps_h]              # ... + checksum
+        n += sum(2 * h.nbytes for h in host[a])
+        for j in w.failed:                                            # a3
+            bad_b, _ = o_ck.verify(snaps_h[j], cks[j])
+            assert len(bad_b) == 0
+            n += snaps_h[j].nbytes
+        new_h = o_lay.reshard([h if al[j] else None for j, h in enumerate(host[a])],   # a4 + a6
+                              [None if al[j] else s for j, s in enumerate(snaps_h)],
+                              w.old_dp, w.new_dp, w.alive_mask, s_starts)
+        nsn = [h.copy() for h in new_h]                               # a7
+        _ = [o_ck.block_checksums(h) for h in nsn]
+        n += sum(2 * h.nbytes for h in new_h)
+        return n
+
+    c0 = time.perf_counter()
+    if threads > 1:
+        with ThreadPoolExecutor(max_workers=threads) as pool:
+            cpu_bytes = sum(pool.map(one_array, list(host)))
+    else:
+        cpu_bytes = sum(one_array(a) for a in host)
+    cpu_s = time.perf_counter() - c0
+    # pack + unpack traffic of the sample under the byte accounting of the unfused GPU path
+    bpe = sum(h[0].itemsize for h in host.values())
+    cpu_bytes += 2 * bpe * (int(s_starts[-1]) + oracle_remote_elems(o_lay, s_starts, w.old_dp, w.new_dp, w.alive_mask))
+    return cpu_bytes, cpu_s
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -346,28 +515,35 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     st = torch.cuda.current_stream().cuda_stream
-    w = configs.ALL[args.workload]()
-    starts = w.unit_starts()
-
     A = list(synth.ARRAYS)
-    es = synth.ELEM_SIZE
+
+    if args.workload == "7b_rank_snapshot":
+        r = rank_snapshot_measure(ew, configs, synth, torch, args.steps, args.warmup)
+        w = r["w"]
+        dom = max(r["kernels"], key=lambda k: r["kernels"][k]["ms"])
+        k = r["kernels"][dom]
+        print(json.dumps({
+            "metric": "reshard+snapshot GB/s on one MI355X and % of HBM peak; time to reshard one stage",
+            "value": round(r["step_bytes"] / r["ms_per_step"] / 1e6, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": round(r["ms_per_step"], 3), "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "u64", "data": "synthetic",
+            "config": {"workload": w.name, "note": w.note, "numel": w.numel, "state_bytes": 14 * w.numel,
+                       "arrays": "bf16 P + fp32 W, M, V"},
+            "path": "ew_snapshot of the four arrays, then ew_verify of the four copies",
+            "kernels": r["kernels"],
+            "roofline": {"kernel": {"snapshot": KERNEL_OF["snapshot_old"], "verify": KERNEL_OF["verify"]}[dom], "bound": "hbm",
+                         "achieved": k["GB/s"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": k["frac_of_peak"],
+                         "traffic": read_traffic(f"ew_{dom}/{w.name}"),
+                         "bytes_per_launch": round(k["GB"] * 1e9 / k["launches"]),
+                         "avg_launch_us": round(k["ms"] / k["launches"] * 1e3, 2)},
+            "cpu_baseline": None}))
+        return
+
+    res = run_stage(args, ew, configs, synth, torch, args.workload)
+    w, starts, head, other = res["w"], res["starts"], res["head"], res["other"]
     numel = w.numel
-    # all four arrays resident at once, except where that exceeds the GPU's memory
-    residency = [[a] for a in A] if w.name == "70b_stage" else [A]
-    parts = []
-    for group in residency:
-        parts.append(measure(args, ew, synth, torch, w, starts, group, keep_state=(len(residency) == 1)))
-        torch.cuda.empty_cache()
-    head = summarise(merge_paths([p["head"] for p in parts]), w.name)
-    other = None if parts[0]["other"] is None else summarise(merge_paths([p["other"] for p in parts]), w.name)
-    copy_gbs = parts[-1]["copy_gbs"]
-    reshard_only_ms = sum(p["reshard_only_ms"] for p in parts)
-    direct_ms = sum(p["direct_ms"] for p in parts)
-    direct_snap_ms = sum(p["direct_snap_ms"] for p in parts)
-    n_remote = parts[0]["n_remote"]
-    old_len = parts[0]["old_len"]
-    old, alive = parts[0]["keep"] if parts[0]["keep"] else (None, None)
-    st = torch.cuda.current_stream().cuda_stream
+    n_remote, old_len = res["n_remote"], res["old_len"]
+    old, alive = res["keep"] if res["keep"] else (None, None)
 
     names = {True: "unfused (ew_unpack, then ew_snapshot of the new shards)",
              False: "fused (ew_unpack_snapshot also writes the new shards' snapshots and checksums)"}
@@ -380,33 +556,33 @@ def main():
                    "new_dp": w.new_dp, "failed": w.failed, "units": int(len(starts) - 1),
                    "remote_fraction": round(n_remote / numel, 4), "arrays": "bf16 P + fp32 W, M, V"},
         "frac_of_hbm_peak": round(head["value"] / HBM_PEAK_GBS, 4),
+        "step_device_ms_min_max": [round(head["step_device_ms_min"], 3), round(head["step_device_ms_max"], 3)],
         "path": names[args.unfused],
-        "reshard_one_stage_ms": round(reshard_only_ms, 3),
-        "reshard_useful_GBps": round(14 * numel / reshard_only_ms / 1e6, 1),
+        "reshard_one_stage_ms": round(res["reshard_only_ms"], 3),
+        "reshard_useful_GBps": round(14 * numel / res["reshard_only_ms"] / 1e6, 1),
         "reshard_without_arena": {
             "note": "ew_reshard: every segment pulled straight from its holder's buffer, for ranks in one address "
                     "space (outside `value`, which keeps the pack -> arena -> unpack path)",
-            "reshard_ms": round(direct_ms, 3), "GBps": round(28 * numel / direct_ms / 1e6, 1),
-            "reshard_plus_new_snapshot_ms": round(direct_snap_ms, 3),
-            "reshard_plus_new_snapshot_GBps": round(42 * numel / direct_snap_ms / 1e6, 1)},
+            "reshard_ms": round(res["direct_ms"], 3), "GBps": round(28 * numel / res["direct_ms"] / 1e6, 1),
+            "reshard_plus_new_snapshot_ms": round(res["direct_snap_ms"], 3),
+            "reshard_plus_new_snapshot_GBps": round(42 * numel / res["direct_snap_ms"] / 1e6, 1)},
         "plan_ms": round(head["plan_ms"], 3),
         "step_GB": round(head["step_GB"], 3),
         "kernels": head["kernels"],
-        "plain_copy_GBps": round(copy_gbs, 1),
+        "plain_copy_GBps": round(res["copy_gbs"], 1),
         "roofline": head["roofline"],
     }
-    if parts[0]["tiny_latency"] is not None:
-        out["tiny_step_latency"] = parts[0]["tiny_latency"]
+    if res["tiny_latency"] is not None:
+        out["tiny_step_latency"] = res["tiny_latency"]
     if other is not None:
         out["other_path"] = {"path": names[not args.unfused], "ms_per_step": round(other["ms_per_step"], 3),
                              "value": round(other["value"], 1), "step_GB": round(other["step_GB"], 3),
                              "kernels": other["kernels"]}
 
-    # ---------------- CPU baseline: the oracle as it stands, one core, on a bounded sample
+    # ---------------- CPU baseline: the oracle as it stands on a bounded sample; nothing of the library is called
     if not args.no_cpu_baseline and old is None:
         out["cpu_baseline"] = None   # measured at the workloads whose state is resident all at once (default: 7b_stage)
     if not args.no_cpu_baseline and old is not None:
-        from oracle import checksum as o_ck
         from oracle import layout as o_lay
         n_units = min(args.cpu_sample_units, len(starts) - 1)
         s_starts = starts[:n_units + 1].astype(np.int64)
@@ -414,39 +590,55 @@ def main():
         s_old_len = o_lay.shard_lengths(s_starts, w.old_dp)
         host = {a: [synth.to_numpy_bits(old[a][j][:s_old_len[j]]) for j in range(w.old_dp)] for a in A}
         torch.cuda.synchronize()
-        al = [bool(x) for x in alive]
-        c0 = time.perf_counter()
-        cpu_bytes = 0
-        for a in A:
-            snaps_h = [h.copy() for h in host[a]]                         # a2: copy ...
-            cks = [o_ck.block_checksums(h) for h in snaps_h]              # ... + checksum
-            cpu_bytes += sum(2 * h.nbytes for h in host[a])
-            for j in w.failed:                                            # a3
-                bad_b, _ = o_ck.verify(snaps_h[j], cks[j])
-                assert len(bad_b) == 0
-                cpu_bytes += snaps_h[j].nbytes
-            new_h = o_lay.reshard([h if al[j] else None for j, h in enumerate(host[a])],   # a4 + a6
-                                  [None if al[j] else s for j, s in enumerate(snaps_h)],
-                                  w.old_dp, w.new_dp, w.alive_mask, s_starts)
-            nsn = [h.copy() for h in new_h]                               # a7
-            _ = [o_ck.block_checksums(h) for h in nsn]
-            cpu_bytes += sum(2 * h.nbytes for h in new_h)
-        cpu_s = time.perf_counter() - c0
-        # pack+unpack traffic of the sample under the byte accounting of the unfused GPU path
-        p_s = ew.ew_plan_bounds(w.old_dp, w.new_dp, w.alive_mask, s_starts.astype(np.uint64))
-        cpu_bytes += 2 * 14 * (s_numel + p_s.stage_len)
-        p_s.close()
+        cpu_bytes, cpu_s = cpu_baseline(w, starts, host, n_units, 1)
         out["cpu_baseline"] = {
             "value": round(cpu_bytes / cpu_s / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
             "sample": f"first {n_units} of {len(starts) - 1} units of {w.name} ({s_numel} elements, all four arrays): "
                       f"numpy oracle snapshot+checksum, verify, reconstruct+slice, snapshot+checksum of the result, "
                       f"bytes counted as for the unfused GPU path; {cpu_s:.1f} s on one host core",
         }
+        cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+        threads = min(len(A), cores)
+        if threads > 1:   # the same oracle, the four state arrays side by side
+            mt_bytes, mt_s = cpu_baseline(w, starts, host, n_units, threads)
+            out["cpu_baseline"]["all_cores_variant"] = {
+                "value": round(mt_bytes / mt_s / 1e9, 3), "unit": "GB/s", "cores": threads, "cores_available": cores,
+                "seconds": round(mt_s, 2), "note": "one host thread per state array (the oracle reshards an array as a whole)"}
         del host
+        # the tiny workload by the same oracle (cache-sized: a latency, like the GPU's)
+        tw = configs.tiny()
+        t_starts = tw.unit_starts()
+        t_len = o_lay.shard_lengths(t_starts.astype(np.int64), tw.old_dp)
+        t_host = {a: [synth.to_numpy_bits(synth.fill(tw.seed, j, a, 0, t_len[j], "cpu")) for j in range(tw.old_dp)] for a in A}
+        t_bytes, t_s = min((cpu_baseline(tw, t_starts, t_host, len(t_starts) - 1, 1) for _ in range(5)), key=lambda r: r[1])
+        out["cpu_baseline"]["tiny"] = {"ms_per_step": round(t_s * 1e3, 3), "value": round(t_bytes / t_s / 1e9, 3),
+                                       "unit": "GB/s", "cores": 1}
+
+    del old, res
+    torch.cuda.empty_cache()
+    # ---------------- the other named workloads, briefly, each on its own (outside the timed region)
+    if not args.no_workloads and w.name == "7b_stage":
+        wl = {}
+        t = run_stage(args, ew, configs, synth, torch, "tiny", steps=20, warmup=3, do_other=False, extras=False)
+        wl["tiny"] = {"note": t["w"].note + "; cache resident and launch bound: latencies, not HBM fractions",
+                      "ms_per_step": round(t["head"]["ms_per_step"], 4), "plan_ms": round(t["head"]["plan_ms"], 4),
+                      "reshard_one_stage_ms": round(t["reshard_only_ms"], 4), "device_part_latency": t["tiny_latency"]}
+        del t
+        r = rank_snapshot_measure(ew, configs, synth, torch, 10, 2)
+        wl["7b_rank_snapshot"] = {"note": r["w"].note, "state_GB": round(14 * r["w"].numel / 1e9, 3),
+                                  "ms_per_step": round(r["ms_per_step"], 4),
+                                  "GBps": round(r["step_bytes"] / r["ms_per_step"] / 1e6, 1), "kernels": r["kernels"]}
+        del r
+        torch.cuda.empty_cache()
+        for name, k in (("13b_stage", 5), ("70b_stage", 3)):
+            t = run_stage(args, ew, configs, synth, torch, name, steps=k, warmup=1, do_other=False, extras=False)
+            wl[name] = compact(t)
+            del t
+            torch.cuda.empty_cache()
+        out["workloads"] = wl
 
     # ---------------- layer migration, contiguous vs interleaved assignment (Sec. 6.3); not part of `value`
     if not args.no_migration and w.name != "tiny":
-        del old, parts
         torch.cuda.empty_cache()
         out["layer_migration"] = migration_compare(ew, configs, synth, torch, st, dev)
     if not args.no_grad_snapshot and w.name != "tiny":

@@ -170,6 +170,14 @@ typedef struct {
 int ew_plan_tiles(const ew_plan_t *plan, int which, uint32_t tile_elems, uint32_t align_elems, uint64_t first,
                   uint64_t count, ew_tile_t *out, uint64_t *total);
 
+/* Which tile of a launch of n_workgroups tiles workgroup `workgroup` copies (the routine the tile
+ * kernels use, on the host: inspection and tests).  Consecutive workgroup ids go round-robin to the
+ * GPU's 8 XCDs, each with an L2 of its own; with group > 1, inside every block of 8*group workgroups
+ * XCD x takes the `group` consecutive tiles x*group .. x*group+group-1, so that each XCD streams
+ * through runs of the destination instead of every eighth tile (the knob "xcd_group_kib" divided
+ * by the tile size is the group the kernels use).  group 0 or 1, and a trailing partial block: identity. */
+uint64_t ew_tile_of_workgroup(uint64_t workgroup, uint64_t n_workgroups, uint32_t group);
+
 /* Builds the copy-tile tables (segments cut into pieces of at most tile_elems elements;
  * 0 = library default, 4 KiB worth of elements) for both element sizes and uploads them to the
  * current device on `stream` (a few hundred KiB for a uniform chunk).  Must precede ew_pack /
@@ -335,7 +343,9 @@ int ew_memcpy(const void *src, void *dst, uint64_t nbytes, void *stream);
  * for ew_verify; 0 / 1 force the slot / atomic kernel for both), "snapshot_wave_min_bytes"
  * (ew_snapshot uses one-wave workgroups from this size on, 256-lane ones below; default 128 MiB),
  * "fused_wgs_per_cu", "verify_wgs_per_cu", "adam_wgs_per_cu" (workgroups resident per CU for the
- * kernels of ew_unpack_snapshot, ew_verify and ew_adam_step; 0 = all that fit; defaults 6, 4, 11),
+ * kernels of ew_unpack_snapshot, ew_verify and ew_adam_step; 0 = all that fit; defaults 0, 4, 11),
+ * "xcd_group_kib" (the tile kernels hand each of the 8 XCDs runs of consecutive tiles of this many
+ * KiB instead of dealing tiles out one by one; 0 = one by one; default 2048),
  * "fused_mode" (0 = default; 1 forces the scratch-free form of ew_unpack_snapshot),
  * "scratch_max_concurrent" (read-only statistic: the most calls that ever held a scratch region at
  * the same time; setting it to 0 resets it).

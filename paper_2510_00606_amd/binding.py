@@ -63,6 +63,7 @@ _SIGNATURES = {
     "ew_plan_num_runs": (C.c_uint64, [C.c_void_p]),
     "ew_plan_tiles": (C.c_int, [C.c_void_p, C.c_int, C.c_uint32, C.c_uint32, C.c_uint64, C.c_uint64, C.c_void_p,
                                 C.POINTER(C.c_uint64)]),
+    "ew_tile_of_workgroup": (C.c_uint64, [C.c_uint64, C.c_uint64, C.c_uint32]),
     "ew_plan_upload": (C.c_int, [C.c_void_p, C.c_uint32, C.c_void_p]),
     "ew_pack": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p]),
     "ew_unpack": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p]),
@@ -266,6 +267,10 @@ def ew_partition_layers(t, mem, cap):
     _check(lib().ew_partition_layers(L, P, t.ctypes.data, mem.ctypes.data, cap.ctypes.data, bounds.ctypes.data,
                                      C.byref(cost)), "ew_partition_layers")
     return cost.value, [int(x) for x in bounds[:P - 1]]
+
+
+def ew_tile_of_workgroup(workgroup: int, n_workgroups: int, group: int) -> int:
+    return int(lib().ew_tile_of_workgroup(workgroup, n_workgroups, group))
 
 
 def ew_plan_upload(plan: Plan, tile_elems: int = 0, stream=None):

@@ -104,7 +104,9 @@ __global__ __launch_bounds__(kThreads) void ew_cksum_kernel(const char *__restri
 // many workgroups onto one checksum record serialise badly.  So: a workgroup of WAVES waves folds its
 // WAVES KiB into one (sum, xor) pair and writes it to its own 16-byte slot of a scratch region (no
 // atomics, no zero-fill), and ew_fold_kernel then folds the slots of every 1 MiB block into the
-// block's record.  WAVES = 1 (the wave folds with DPP moves, lane 63 writes the slot: no LDS, no
+// block's record.  Workgroup i takes KiB i of the buffer: handing each XCD runs of consecutive chunks,
+// which pays for the tile kernels (xcd_remap), costs this kernel and the plain copy 1-5 %.
+// WAVES = 1 (the wave folds with DPP moves, lane 63 writes the slot: no LDS, no
 // barrier) is the faster shape for large buffers (6.45 against 6.32 TB/s on 0.875 GB); WAVES = 4
 // (the four waves meet in LDS) has a quarter of the workgroups and slots and is a little quicker
 // below about 100 MiB, where launch and drain times weigh more (9.2 against 9.8 us for 1 MiB).
@@ -113,12 +115,17 @@ __global__ __launch_bounds__(64 * WAVES) void ew_cksum_slots_kernel(const u32x4 
                                                                     u32x4 *__restrict__ dst, uint64_t nbytes,
                                                                     ew_cksum_t *__restrict__ slots) {
   static_assert(WAVES == 1 || 64 * WAVES == kThreads, "block_fold is written for kThreads lanes");
-  const uint64_t i = (uint64_t)blockIdx.x * (64 * WAVES) + threadIdx.x;
+  const uint64_t first = (uint64_t)blockIdx.x * (64 * WAVES);  // the workgroup's first vector
+  const uint64_t i = first + threadIdx.x;
   const uint64_t nvec = nbytes >> 4;
   uint64_t sum = 0, xr = 0;
   if (i < nvec) {
     const u32x4 v = load16(src + i);
-    if (COPY) store16(dst + i, v);
+    if (COPY) {
+      const uint64_t left = nvec - first;
+      const ew::StoreWindow<> out(dst + first, (uint32_t)(left < 64 * WAVES ? left : 64 * WAVES) << 4);
+      out.put(threadIdx.x << 4, v);
+    }
     fold(v, sum, xr);
   } else if (i == nvec && (nbytes & 15u)) {
     // fewer than 16 trailing bytes: copied and folded as up to two zero-padded words

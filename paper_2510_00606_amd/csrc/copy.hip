@@ -32,24 +32,24 @@ using ew::u32x4;
 // lets the compiler keep the decode on the scalar unit (a persistent loop forces vector loads of
 // the tables, since a store might alias them: 3.9 instead of 6.2 TB/s).
 template <int ES>
-__global__ __launch_bounds__(kThreads) void ew_segcopy_kernel(TableRef table, CopyTabs tabs) {
-  const ew::TileRef tl = ew::decode_tile(table, blockIdx.x);
+__global__ __launch_bounds__(kThreads) void ew_segcopy_kernel(TableRef table, CopyTabs tabs, uint32_t xcd_group) {
+  const ew::TileRef tl = ew::decode_tile(table, ew::xcd_remap(blockIdx.x, gridDim.x, xcd_group));
   const char *s = tabs.src[tl.src_buf] + tl.src_off * ES;
   char *d = tabs.dst[tl.dst_buf] + tl.dst_off * ES;
   const uint32_t nbytes = tl.len * ES;
   if ((((uintptr_t)s | (uintptr_t)d) & 15u) == 0) {
     const u32x4 *sv = reinterpret_cast<const u32x4 *>(s);
-    u32x4 *dv = reinterpret_cast<u32x4 *>(d);
     const uint32_t nvec = nbytes >> 4;
+    const ew::StoreWindow<> out(d, nvec << 4);
     uint32_t i = threadIdx.x;
     for (; i + (kUnroll - 1) * kThreads < nvec; i += kUnroll * kThreads) {  // tiles above 12 KiB only
       u32x4 v[kUnroll];
 #pragma unroll
       for (int u = 0; u < kUnroll; ++u) v[u] = load16(sv + i + u * kThreads);
 #pragma unroll
-      for (int u = 0; u < kUnroll; ++u) store16(dv + i + u * kThreads, v[u]);
+      for (int u = 0; u < kUnroll; ++u) out.put((i + u * kThreads) << 4, v[u]);
     }
-    for (; i < nvec; i += kThreads) store16(dv + i, load16(sv + i));
+    for (; i < nvec; i += kThreads) out.put(i << 4, load16(sv + i));
     // fewer than 16 trailing bytes: whole elements, one per lane
     const uint32_t done = nvec << 4;
     const uint32_t rem = (nbytes - done) / ES;
@@ -80,8 +80,10 @@ __global__ __launch_bounds__(kThreads) void ew_segcopy_kernel(TableRef table, Co
 constexpr int kCopyThreads = 64;
 __global__ __launch_bounds__(kCopyThreads) void ew_copy_kernel(const u32x4 *__restrict__ src,
                                                                u32x4 *__restrict__ dst, uint64_t nvec) {
-  const uint64_t i = (uint64_t)blockIdx.x * kCopyThreads + threadIdx.x;
-  if (i < nvec) store16(dst + i, load16(src + i));
+  const uint64_t first = (uint64_t)blockIdx.x * kCopyThreads;  // the workgroup's first vector
+  const uint64_t left = nvec - first;
+  const ew::StoreWindow<> out(dst + first, (uint32_t)(left < kCopyThreads ? left : kCopyThreads) << 4);
+  if (threadIdx.x < left) out.put(threadIdx.x << 4, load16(src + first + threadIdx.x));
 }
 
 void release_tables(ew_plan_t *plan) {
@@ -97,10 +99,11 @@ void release_tables(ew_plan_t *plan) {
 int launch_segcopy(const ew::TileTable &tt, const CopyTabs &tabs, uint32_t elem_size, hipStream_t stream) {
   if (tt.ntiles == 0) return EW_OK;
   const uint32_t grid = (uint32_t)tt.ntiles;  // ew_plan_upload refuses tables above 2^31-1 tiles
+  const uint32_t g = ew::xcd_group_for((uint64_t)tt.tile_bytes);
   if (elem_size == 2)
-    hipLaunchKernelGGL(ew_segcopy_kernel<2>, dim3(grid), dim3(kThreads), 0, stream, tt.dev, tabs);
+    hipLaunchKernelGGL(ew_segcopy_kernel<2>, dim3(grid), dim3(kThreads), 0, stream, tt.dev, tabs, g);
   else
-    hipLaunchKernelGGL(ew_segcopy_kernel<4>, dim3(grid), dim3(kThreads), 0, stream, tt.dev, tabs);
+    hipLaunchKernelGGL(ew_segcopy_kernel<4>, dim3(grid), dim3(kThreads), 0, stream, tt.dev, tabs, g);
   EW_HIP(hipGetLastError());
   return EW_OK;
 }
@@ -149,6 +152,7 @@ int ew_plan_upload(ew_plan_t *plan, uint32_t tile_elems, void *stream) {
       for (int w = 0; w < ew::kNumTables; ++w) {
         ew::TileTable &tt = plan->tables[w][e];
         ew::build_tile_table(*plan, w, plan->tile_elems[e], (uint32_t)(knob_align / es), tt);
+        tt.tile_bytes = plan->tile_elems[e] * es;
         if (tt.ntiles > 0x7fffffffull) {  // tile ids are workgroup ids
           release_tables(plan);
           return EW_EINVAL;

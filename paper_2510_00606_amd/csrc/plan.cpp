@@ -522,4 +522,8 @@ uint64_t ew_plan_pair_off(const ew_plan_t *p, uint32_t h, uint32_t k) {
   return (p && h < p->old_dp && k < p->new_dp) ? p->pair_off[(size_t)h * p->new_dp + k] : 0;
 }
 
+uint64_t ew_tile_of_workgroup(uint64_t workgroup, uint64_t n_workgroups, uint32_t group) {
+  return ew::xcd_remap(workgroup, n_workgroups, group);
+}
+
 }  // extern "C"

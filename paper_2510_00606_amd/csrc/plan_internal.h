@@ -103,12 +103,27 @@ EW_HD TileRef decode_tile(const TableRef &tb, uint64_t t) {
   return ref;
 }
 
+// Which tile workgroup w of an n-workgroup launch takes.  The hardware deals consecutive workgroup ids
+// round-robin to the 8 XCDs, each with an L2 of its own, so with the identity mapping two neighbouring
+// tiles never share an L2, and a 128-byte line that both touch (sources are only 32-byte aligned
+// relative to the destination-aligned cuts) is fetched from memory twice.  With group g > 1, inside
+// every block of 8*g consecutive workgroups XCD x takes the g consecutive tiles x*g .. x*g+g-1; the
+// launch as a whole still walks the tiles in order.  A trailing partial block keeps the identity.
+EW_HD uint64_t xcd_remap(uint64_t w, uint64_t n, uint32_t g) {
+  if (g <= 1) return w;
+  const uint64_t blk = 8ull * g, base = w / blk * blk;
+  if (base + blk > n) return w;
+  const uint64_t r = w - base;
+  return base + (r & 7) * g + (r >> 3);
+}
+
 struct TileTable {       // host-side description of one (which, elem size) table
   std::vector<RunT> runs;
   std::vector<TileT> templ;
   std::vector<uint32_t> coarse;
   uint32_t shift = 0;
   uint64_t ntiles = 0;
+  uint32_t tile_bytes = 0;  // nominal size of a tile (most tiles have it; none is larger)
   TableRef host_ref() const {
     return TableRef{runs.data(), coarse.data(), templ.data(), (uint32_t)runs.size(), shift};
   }

@@ -36,9 +36,11 @@ struct Knobs {
   Knob tile_bytes{4096};        // default copy tile: 256 lanes x one 128-bit vector
   Knob tile_elems{0};           // > 0 overrides tile_bytes with a size in elements
   Knob tile_align_bytes{128};   // tile cuts fall on multiples of this in the destination (0: off)
-  // Caps on the workgroups resident per CU (0 = all that fit) for the kernels that keep three or more
-  // HBM streams busy, or that read only: they run faster with fewer requests in flight.
-  Knob fused_wgs_per_cu{6};     // fused unpack + snapshot (256 lanes; 8 fit)
+  Knob xcd_group_kib{2048};     // KiB of consecutive tiles that one XCD takes (see xcd_remap); 0 = identity
+  // Caps on the workgroups resident per CU (0 = all that fit) for the kernels that run faster with
+  // fewer requests in flight.
+  Knob fused_wgs_per_cu{0};     // fused unpack + snapshot (256 lanes; 8 fit): no cap since tiles go to XCDs in
+                                // runs (with the identity mapping six per CU were 1-5 % faster than eight)
   Knob fused_mode{0};           // fused unpack + snapshot: 0 = slot per tile + fold kernel, 1 = scratch-free (atomics)
   Knob verify_wgs_per_cu{4};    // read-only streaming checksum (256 lanes; 8 fit)
   Knob adam_wgs_per_cu{11};     // optimizer step (one wave per workgroup; 32 fit)
@@ -46,6 +48,10 @@ struct Knobs {
 Knobs &knobs();
 
 int num_cus();
+
+// The group argument of xcd_remap for a kernel whose workgroups each cover unit_bytes of the
+// destination (knob xcd_group_kib; 1 = identity).
+uint32_t xcd_group_for(uint64_t unit_bytes);
 
 // Dynamic LDS bytes that, requested per workgroup of a kernel with `static_lds` bytes of its own,
 // leave room for exactly `wgs_per_cu` workgroups on a CU of the current device; 0 when no cap is

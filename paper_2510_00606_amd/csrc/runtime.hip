@@ -90,6 +90,13 @@ int num_cus() {
   return n;
 }
 
+uint32_t xcd_group_for(uint64_t unit_bytes) {
+  const uint64_t kib = (uint64_t)g_knobs.xcd_group_kib.load();
+  if (kib == 0 || unit_bytes == 0) return 1;
+  const uint64_t g = kib * 1024 / unit_bytes;
+  return g < 1 ? 1u : (g > (1u << 24) ? (1u << 24) : (uint32_t)g);
+}
+
 uint32_t occupancy_pad(int64_t wgs_per_cu, uint32_t static_lds) {
   if (wgs_per_cu <= 0 || wgs_per_cu > 64) return 0;
   static std::atomic<int> cached[kMaxDevices];  // LDS bytes per CU
@@ -296,6 +303,9 @@ int ew_set_param(const char *name, int64_t value) {
   } else if (!std::strcmp(name, "fused_wgs_per_cu")) {
     if (value < 0 || value > 8) return EW_EINVAL;
     k.fused_wgs_per_cu = value;
+  } else if (!std::strcmp(name, "xcd_group_kib")) {
+    if (value < 0 || value > (1 << 20)) return EW_EINVAL;
+    k.xcd_group_kib = value;
   } else if (!std::strcmp(name, "fused_mode")) {
     if (value < 0 || value > 1) return EW_EINVAL;
     k.fused_mode = value;
@@ -328,6 +338,7 @@ int64_t ew_get_param(const char *name) {
   if (!std::strcmp(name, "tile_bytes")) return k.tile_bytes;
   if (!std::strcmp(name, "tile_align_bytes")) return k.tile_align_bytes;
   if (!std::strcmp(name, "fused_wgs_per_cu")) return k.fused_wgs_per_cu;
+  if (!std::strcmp(name, "xcd_group_kib")) return k.xcd_group_kib;
   if (!std::strcmp(name, "fused_mode")) return k.fused_mode;
   if (!std::strcmp(name, "verify_wgs_per_cu")) return k.verify_wgs_per_cu;
   if (!std::strcmp(name, "adam_wgs_per_cu")) return k.adam_wgs_per_cu;

@@ -17,6 +17,14 @@
 #include "device_util.h"
 #include "runtime.h"
 
+// cache policy of the store to the new shard and of the store to its snapshot copy (see StoreWindow)
+#ifndef EW_FUSED_AUX1
+#define EW_FUSED_AUX1 2
+#endif
+#ifndef EW_FUSED_AUX2
+#define EW_FUSED_AUX2 2
+#endif
+
 namespace {
 
 using ew::block_fold;
@@ -41,11 +49,13 @@ __device__ __forceinline__ void add_to_record(ew_cksum_t *rec, uint64_t sum, uin
 
 template <int ES, bool SLOTS>
 __global__ __launch_bounds__(kThreads) void ew_unpack_snap_kernel(TableRef table, uint64_t tile_base, CopyTabs tabs,
-                                                                  SnapTabs st, ew_cksum_t *__restrict__ slots) {
+                                                                  SnapTabs st, ew_cksum_t *__restrict__ slots,
+                                                                  uint32_t xcd_group) {
   __shared__ uint64_t lds_sum[kThreads / 64], lds_xor[kThreads / 64];
   __shared__ uint64_t lds_sum_hi[kThreads / 64], lds_xor_hi[kThreads / 64];
   typedef typename std::conditional<ES == 2, uint16_t, uint32_t>::type elem_t;
-  const ew::TileRef tl = ew::decode_tile(table, tile_base + blockIdx.x);
+  const uint64_t tile = ew::xcd_remap(blockIdx.x, gridDim.x, xcd_group);  // of this pass
+  const ew::TileRef tl = ew::decode_tile(table, tile_base + tile);
   const char *s = tabs.src[tl.src_buf] + tl.src_off * ES;
   const uint64_t dbyte = tl.dst_off * ES;  // byte offset inside the new shard
   char *d = tabs.dst[tl.dst_buf] + dbyte;
@@ -56,13 +66,13 @@ __global__ __launch_bounds__(kThreads) void ew_unpack_snap_kernel(TableRef table
   uint64_t sum = 0, xr = 0, sum_hi = 0, xr_hi = 0;
   if ((((uintptr_t)s | (uintptr_t)d | (uintptr_t)d2 | dbyte) & 15u) == 0) {
     const u32x4 *sv = reinterpret_cast<const u32x4 *>(s);
-    u32x4 *dv = reinterpret_cast<u32x4 *>(d);
-    u32x4 *d2v = reinterpret_cast<u32x4 *>(d2);
     const uint32_t nvec = nbytes >> 4;
+    const ew::StoreWindow<EW_FUSED_AUX1> out(d, nvec << 4);
+    const ew::StoreWindow<EW_FUSED_AUX2> out2(d2, nvec << 4);
     for (uint32_t i = threadIdx.x; i < nvec; i += kThreads) {  // one trip for the default 4 KiB tile
       const u32x4 v = load16(sv + i);
-      store16(dv + i, v);
-      store16(d2v + i, v);
+      out.put(i << 4, v);
+      out2.put(i << 4, v);
       if (straddle && dbyte + 16ull * i >= boundary)
         fold(v, sum_hi, xr_hi);
       else
@@ -109,7 +119,7 @@ __global__ __launch_bounds__(kThreads) void ew_unpack_snap_kernel(TableRef table
       ew_cksum_t r;
       r.sum = sum;
       r.xr = xr;
-      slots[blockIdx.x] = r;
+      slots[tile] = r;
     } else {
       add_to_record(st.rec[tl.dst_buf] + (dbyte >> 20), sum, xr);
     }
@@ -163,20 +173,20 @@ int launch_pass(const ew::TileTable &tt, uint64_t t0, uint64_t n, const CopyTabs
                 ew_cksum_t *slots, hipStream_t stream) {
   constexpr uint32_t kTilesPerLane = 16;
   const uint64_t fold_grid = ((n + kTilesPerLane - 1) / kTilesPerLane + kThreads - 1) / kThreads;
-  // Three HBM streams per workgroup (one read, two writes): with six workgroups resident per CU
-  // instead of the eight that fit, fewer DRAM rows are contended for at a time and the kernel runs
-  // 1-5 % faster (measured in one process, same buffers: 5.58 -> 5.84 TB/s in a slow placement of the
-  // buffers, 6.04 -> 6.09 in a fast one; five per CU gains more in the slow case and loses in the
-  // fast one, four loses in both).  The cap is set by asking for unused dynamic LDS.
+  // Resident workgroups per CU can be capped by asking for unused dynamic LDS (knob fused_wgs_per_cu).
+  // With tiles dealt to the XCDs one by one, six per CU were 1-5 % faster than the eight that fit
+  // (three HBM streams per workgroup); with runs of tiles per XCD (xcd_remap) all eight are best
+  // (7b stage, fp32: 5.97 / 5.98 / 5.85 / 5.62 TB/s at 8 / 7 / 6 / 5 per CU), so no cap by default.
   const uint32_t lds_pad = ew::occupancy_pad(ew::knobs().fused_wgs_per_cu, 8 * sizeof(uint64_t) * (kThreads / 64));
+  const uint32_t xcd_group = ew::xcd_group_for((uint64_t)tt.tile_bytes);
   if (!slots) {  // no scratch region: the workgroups add to the records themselves
     hipLaunchKernelGGL((ew_unpack_snap_kernel<ES, false>), dim3((uint32_t)n), dim3(kThreads), lds_pad, stream, tt.dev,
-                       t0, tabs, st, slots);
+                       t0, tabs, st, slots, xcd_group);
     EW_HIP(hipGetLastError());
     return EW_OK;
   }
   hipLaunchKernelGGL((ew_unpack_snap_kernel<ES, true>), dim3((uint32_t)n), dim3(kThreads), lds_pad, stream, tt.dev, t0,
-                     tabs, st, slots);
+                     tabs, st, slots, xcd_group);
   EW_HIP(hipGetLastError());
   hipLaunchKernelGGL(ew_fold_tiles_kernel<ES>, dim3((uint32_t)fold_grid), dim3(kThreads), 0, stream, tt.dev, t0, n,
                      kTilesPerLane, st, slots);

@@ -18,7 +18,7 @@ MIB = 1 << 20
 def default_params():
     saved = {k: ew.ew_get_param(k) for k in ("tile_bytes", "tile_elems", "tile_align_bytes", "cksum_sub_bytes", "cksum_wgs_per_cu",
                                               "cksum_mode", "fused_wgs_per_cu", "fused_mode", "verify_wgs_per_cu",
-                                              "snapshot_wave_min_bytes")}
+                                              "snapshot_wave_min_bytes", "xcd_group_kib")}
     yield
     for k, v in saved.items():
         ew.ew_set_param(k, v)
@@ -327,6 +327,20 @@ def test_fused_unpack_with_occupancy_caps(wgs):
     for es in (2, 4):
         reshard_case(8, 7, 0xFF & ~(1 << 5), 3_000_000 + 8 * 37, 262144, es, rng)
         reshard_case(3, 2, 0b111, 2_600_000, 99_992, es, rng)
+
+
+@pytest.mark.parametrize("kib", [0, 4, 8, 12, 64, 2048, 1 << 20])
+def test_tiles_dealt_to_xcds_in_runs(kib):
+    """The workgroup -> tile mapping (runs of consecutive tiles per XCD) permutes who copies which tile,
+    never what is copied: every group size, also ones that do not divide the number of tiles, tiles
+    that are smaller than nominal, and groups larger than the launch."""
+    ew.ew_set_param("xcd_group_kib", kib)
+    rng = np.random.default_rng(500 + kib)
+    for es in (2, 4):
+        reshard_case(8, 7, 0xFF & ~(1 << 5), 3_000_000 + 8 * 37, 262144, es, rng)
+        reshard_case(3, 2, 0b111, 2_600_000, 99_992, es, rng)
+        reshard_case(6, 4, 0b111011, 999_999, 10_007, es, rng, tile_elems=1000)
+        reshard_case(4, 3, 0b1011, 4099, 264, es, rng)
 
 
 def test_fused_unpack_scratch_free_form():

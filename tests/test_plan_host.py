@@ -71,13 +71,13 @@ def test_error_codes():
         ew.ew_set_param("no_such_knob", 1)
     with pytest.raises(ew.EwError):
         ew.ew_set_param("cksum_sub_bytes", 3000)
-    assert ew.ew_get_param("fused_wgs_per_cu") == 6 and ew.ew_get_param("no_such_knob") == -1
+    assert ew.ew_get_param("xcd_group_kib") == 2048 and ew.ew_get_param("no_such_knob") == -1
     for bad in (-1, 9):
         with pytest.raises(ew.EwError):
             ew.ew_set_param("fused_wgs_per_cu", bad)
     ew.ew_set_param("fused_wgs_per_cu", 4)
     assert ew.ew_get_param("fused_wgs_per_cu") == 4
-    ew.ew_set_param("fused_wgs_per_cu", 6)
+    ew.ew_set_param("fused_wgs_per_cu", 0)
 
 
 def test_max_degree_and_wide_mask():
@@ -514,3 +514,23 @@ def test_random_boundaries_and_memberships_match_the_oracle():
         check_tiles(p, 64, 16)
 
     run()
+
+
+def test_xcd_remap_is_a_permutation_of_every_launch():
+    """The workgroup -> tile mapping of the tile kernels, checked through the library's own decoder on
+    the host: for every launch size and group size the mapped ids are a permutation of 0..n-1, runs of
+    `group` consecutive tiles land on one residue class mod 8 (one XCD), and a trailing partial block
+    keeps the identity."""
+    fn = ew.ew_tile_of_workgroup
+    for n in (0, 1, 7, 8, 9, 63, 64, 65, 511, 512, 513, 1000, 4097):
+        for g in (0, 1, 2, 3, 8, 64, 512, 5000):
+            got = [fn(w, n, g) for w in range(n)]
+            assert sorted(got) == list(range(n)), (n, g)
+            if g > 1:
+                blk = 8 * g
+                for w in range(n):
+                    base = w // blk * blk
+                    if base + blk <= n:      # full block: XCD w % 8 owns tiles base + (w%8)*g .. +g-1
+                        assert (got[w] - base) // g == w % 8
+                    else:
+                        assert got[w] == w
