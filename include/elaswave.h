@@ -341,7 +341,8 @@ int ew_memcpy(const void *src, void *dst, uint64_t nbytes, void *stream);
  * so setting one while other threads launch is safe; defaults are the tuned ones).  Names: "tile_bytes", "tile_elems", "tile_align_bytes", "cksum_sub_bytes",
  * "cksum_wgs_per_cu", "cksum_mode" (-1 = default: slot kernel + fold for ew_snapshot, atomic kernel
  * for ew_verify; 0 / 1 force the slot / atomic kernel for both), "snapshot_wave_min_bytes"
- * (ew_snapshot uses one-wave workgroups from this size on, 256-lane ones below; default 128 MiB),
+ * (ew_snapshot uses one-wave workgroups from this size on, 256-lane ones below; default: never),
+ * "snapshot_xcd_group_kib" (ew_snapshot's chunks go to the XCDs in runs of this many KiB; default 128),
  * "fused_wgs_per_cu", "verify_wgs_per_cu", "adam_wgs_per_cu" (workgroups resident per CU for the
  * kernels of ew_unpack_snapshot, ew_verify and ew_adam_step; 0 = all that fit; defaults 0, 4, 11),
  * "xcd_group_kib" (the tile kernels hand each of the 8 XCDs runs of consecutive tiles of this many

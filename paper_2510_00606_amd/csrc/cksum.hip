@@ -104,18 +104,20 @@ __global__ __launch_bounds__(kThreads) void ew_cksum_kernel(const char *__restri
 // many workgroups onto one checksum record serialise badly.  So: a workgroup of WAVES waves folds its
 // WAVES KiB into one (sum, xor) pair and writes it to its own 16-byte slot of a scratch region (no
 // atomics, no zero-fill), and ew_fold_kernel then folds the slots of every 1 MiB block into the
-// block's record.  Workgroup i takes KiB i of the buffer: handing each XCD runs of consecutive chunks,
-// which pays for the tile kernels (xcd_remap), costs this kernel and the plain copy 1-5 %.
-// WAVES = 1 (the wave folds with DPP moves, lane 63 writes the slot: no LDS, no
-// barrier) is the faster shape for large buffers (6.45 against 6.32 TB/s on 0.875 GB); WAVES = 4
-// (the four waves meet in LDS) has a quarter of the workgroups and slots and is a little quicker
-// below about 100 MiB, where launch and drain times weigh more (9.2 against 9.8 us for 1 MiB).
+// block's record.  Two shapes: WAVES = 4 (the four waves meet in LDS; one slot per 4 KiB) and
+// WAVES = 1 (the wave folds with DPP moves, lane 63 writes the slot: no LDS, no barrier; one slot per
+// KiB).  Chunks go to the 8 XCDs in runs (xcd_remap, knob snapshot_xcd_group_kib).  Measured on
+// 0.875 GB buffers, calls back to back, TB/s read + written: chunks dealt out one by one 6.58 (one
+// wave) and 6.52 (four waves); runs of 128 KiB 6.60 and 6.63, runs of 16-32 KiB 6.0, runs of 8 MiB
+// 6.05-6.3.  Four waves with runs of 128 KiB is the default for every size (+0.5 % at 0.875 GB, +1.5 %
+// at 0.44 and 1 GB, +1 % at 100 MiB over one wave dealt one by one, and a quarter of the slots).
 template <bool COPY, int WAVES>
 __global__ __launch_bounds__(64 * WAVES) void ew_cksum_slots_kernel(const u32x4 *__restrict__ src,
                                                                     u32x4 *__restrict__ dst, uint64_t nbytes,
-                                                                    ew_cksum_t *__restrict__ slots) {
+                                                                    ew_cksum_t *__restrict__ slots, uint32_t xcd_group) {
   static_assert(WAVES == 1 || 64 * WAVES == kThreads, "block_fold is written for kThreads lanes");
-  const uint64_t first = (uint64_t)blockIdx.x * (64 * WAVES);  // the workgroup's first vector
+  const uint64_t chunk = ew::xcd_remap(blockIdx.x, gridDim.x, xcd_group);  // which WAVES KiB of the buffer
+  const uint64_t first = chunk * (64 * WAVES);  // the workgroup's first vector
   const uint64_t i = first + threadIdx.x;
   const uint64_t nvec = nbytes >> 4;
   uint64_t sum = 0, xr = 0;
@@ -152,7 +154,7 @@ __global__ __launch_bounds__(64 * WAVES) void ew_cksum_slots_kernel(const u32x4 
   ew_cksum_t r;
   r.sum = sum;
   r.xr = xr;
-  slots[blockIdx.x] = r;
+  slots[chunk] = r;
 }
 
 // One workgroup per checksum block: folds the block's slots (per_block for a full block) into out[b].
@@ -261,6 +263,8 @@ int launch_cksum_slots(const void *src, void *dst, uint64_t nbytes, ew_cksum_t *
   const bool one_wave = nbytes >= (uint64_t)ew::knobs().snapshot_wave_min_bytes;
   const uint64_t slot_bytes = one_wave ? 1024 : 4096;
   const uint64_t pass_bytes = max_slots * slot_bytes;  // what the slots cover; a multiple of 1 MiB
+  const uint64_t group_kib = (uint64_t)ew::knobs().snapshot_xcd_group_kib;
+  const uint32_t xcd_group = group_kib ? (uint32_t)(group_kib * 1024 / slot_bytes) : 1u;
   for (uint64_t off = 0; off < nbytes; off += pass_bytes) {
     const uint64_t n = nbytes - off < pass_bytes ? nbytes - off : pass_bytes;
     // a partial trailing vector belongs to lane n/16, which the last workgroup always contains because
@@ -270,9 +274,11 @@ int launch_cksum_slots(const void *src, void *dst, uint64_t nbytes, ew_cksum_t *
     const u32x4 *s = (const u32x4 *)((const char *)src + off);
     u32x4 *d = (u32x4 *)(COPY ? (char *)dst + off : nullptr);
     if (one_wave)
-      hipLaunchKernelGGL((ew_cksum_slots_kernel<COPY, 1>), dim3((uint32_t)grid), dim3(64), 0, stream, s, d, n, slots);
+      hipLaunchKernelGGL((ew_cksum_slots_kernel<COPY, 1>), dim3((uint32_t)grid), dim3(64), 0, stream, s, d, n, slots,
+                         xcd_group);
     else
-      hipLaunchKernelGGL((ew_cksum_slots_kernel<COPY, 4>), dim3((uint32_t)grid), dim3(256), 0, stream, s, d, n, slots);
+      hipLaunchKernelGGL((ew_cksum_slots_kernel<COPY, 4>), dim3((uint32_t)grid), dim3(256), 0, stream, s, d, n, slots,
+                         xcd_group);
     EW_HIP(hipGetLastError());
     hipLaunchKernelGGL(ew_fold_kernel, dim3((uint32_t)nblk), dim3(kThreads), 0, stream, slots, grid,
                        (uint32_t)(EW_CKSUM_BLOCK / slot_bytes), out + off / EW_CKSUM_BLOCK);

@@ -32,7 +32,9 @@ struct Knobs {
                                 // else a persistent grid of this many workgroups per CU
   Knob cksum_mode{-1};          // -1 = slot kernel + fold for snapshot, streaming kernel for verify;
                                 // 0 / 1 force the slot / streaming kernel for both
-  Knob snapshot_wave_min_bytes{128 << 20};  // snapshot: one-wave workgroups from this size on, 256 lanes below
+  Knob snapshot_wave_min_bytes{(int64_t)1 << 62};  // snapshot: one-wave workgroups from this size on, 256 lanes below
+                                                    // (default: never; see ew_cksum_slots_kernel)
+  Knob snapshot_xcd_group_kib{128};  // snapshot slot kernel: KiB of consecutive chunks per XCD (0 = one by one)
   Knob tile_bytes{4096};        // default copy tile: 256 lanes x one 128-bit vector
   Knob tile_elems{0};           // > 0 overrides tile_bytes with a size in elements
   Knob tile_align_bytes{128};   // tile cuts fall on multiples of this in the destination (0: off)

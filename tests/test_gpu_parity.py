@@ -18,7 +18,7 @@ MIB = 1 << 20
 def default_params():
     saved = {k: ew.ew_get_param(k) for k in ("tile_bytes", "tile_elems", "tile_align_bytes", "cksum_sub_bytes", "cksum_wgs_per_cu",
                                               "cksum_mode", "fused_wgs_per_cu", "fused_mode", "verify_wgs_per_cu",
-                                              "snapshot_wave_min_bytes", "xcd_group_kib")}
+                                              "snapshot_wave_min_bytes", "xcd_group_kib", "snapshot_xcd_group_kib")}
     yield
     for k, v in saved.items():
         ew.ew_set_param(k, v)
@@ -58,6 +58,18 @@ def test_snapshot_one_wave_shape_on_small_buffers(nbytes):
     """The shape meant for large buffers, forced on every size."""
     ew.ew_set_param("snapshot_wave_min_bytes", 0)
     snapshot_case(nbytes, np.random.default_rng(nbytes + 1))
+
+
+@pytest.mark.parametrize("kib", [0, 4, 12, 128, 1 << 20])
+@pytest.mark.parametrize("wave_min", [0, 1 << 62])
+def test_snapshot_chunks_dealt_to_xcds_in_runs(kib, wave_min):
+    """Runs of chunks per XCD permute which workgroup takes which chunk (and which slot it writes),
+    never the result: both workgroup shapes, run lengths that do not divide the launch, runs longer
+    than the launch."""
+    ew.ew_set_param("snapshot_xcd_group_kib", kib)
+    ew.ew_set_param("snapshot_wave_min_bytes", wave_min)
+    for nbytes in (1, 4097, MIB - 8, 3 * MIB + 12345, 17 * MIB + 65536 + 24):
+        snapshot_case(nbytes, np.random.default_rng(kib + nbytes))
 
 
 @pytest.mark.parametrize("sub,wgs", [(4096, 0), (16384, 2), (65536, 0), (262144, 1), (MIB, 0), (MIB, 3)])

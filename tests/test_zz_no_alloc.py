@@ -16,6 +16,13 @@ pytestmark = pytest.mark.gpu
 MIB = 1 << 20
 
 
+@pytest.fixture(autouse=True)
+def default_shape():
+    saved = ew.ew_get_param("snapshot_wave_min_bytes")
+    yield
+    ew.ew_set_param("snapshot_wave_min_bytes", saved)
+
+
 def both_entry_points(nbytes, seed, shift=0):
     """Runs ew_snapshot_noalloc and ew_snapshot on the same seeded bytes; returns nothing, asserts."""
     g = torch.Generator(device=DEV)
@@ -41,16 +48,22 @@ def both_entry_points(nbytes, seed, shift=0):
     assert (got[nb] == np.uint64((1 << 64) - 1)).all(), "record past the end was written"
 
 
-def test_two_calls_in_a_row_second_smaller():
-    both_entry_points(300 * MIB + 3 * 4096 + 5, 1)     # one-wave shape, ragged tail, 307 k slots
-    both_entry_points(37 * MIB + 1024 + 9, 2)          # 256-lane shape, far fewer slots
+@pytest.mark.parametrize("wave_min", [1 << 62, 0])     # 256-lane workgroups (the default) / one-wave workgroups
+def test_two_calls_in_a_row_second_smaller(wave_min):
+    ew.ew_set_param("snapshot_wave_min_bytes", wave_min)
+    both_entry_points(300 * MIB + 3 * 4096 + 5, 1)     # ragged tail; 77 k slots (307 k with one-wave workgroups)
+    both_entry_points(37 * MIB + 1024 + 9, 2)          # far fewer slots: what the first call left must not leak in
     both_entry_points(MIB + 16, 3)
     both_entry_points(5, 4)
 
 
 def test_largest_size_then_a_small_one():
-    both_entry_points(ew.EW_NOALLOC_MAX_BYTES, 5)      # every slot of the array in use
+    ew.ew_set_param("snapshot_wave_min_bytes", 0)      # one slot per KiB: every slot of the array in use
+    both_entry_points(ew.EW_NOALLOC_MAX_BYTES, 5)
     both_entry_points(2 * MIB - 8, 6)
+    ew.ew_set_param("snapshot_wave_min_bytes", 1 << 62)
+    both_entry_points(ew.EW_NOALLOC_MAX_BYTES, 7)
+    both_entry_points(3 * MIB + 40, 8)
 
 
 def test_unaligned_buffers_take_the_scratch_free_kernel():
