@@ -22,7 +22,9 @@ using ew::u32x4;
 // workgroup streams one sub-block, folding its words into (sum, xor) per lane, then across the
 // workgroup.  With sub < 1 MiB the partial results of a block meet in its record through 64-bit
 // atomics (the records are zeroed first).  Serves any alignment; it is the fast form for read-only
-// passes and the fallback for copies.
+// passes and the fallback for copies.  (Dealing the sub-blocks to the XCDs in runs, which pays for the
+// tile kernels and a little for the slot kernel below, changes nothing here: 6.26-6.43 TB/s for runs
+// of 0-4 MiB at 64 KiB sub-blocks and four workgroups per CU.)
 template <bool COPY, bool ALIGNED>
 __global__ __launch_bounds__(kThreads) void ew_cksum_kernel(const char *__restrict__ src, char *__restrict__ dst,
                                                             uint64_t nbytes, ew_cksum_t *out, uint32_t sub,
