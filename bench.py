@@ -65,6 +65,11 @@ def parse():
     return ap.parse_args()
 
 
+def log(msg):
+    """Progress on stderr (stdout carries the one JSON line): long runs must not look hung."""
+    print(f"bench: {msg}", file=sys.stderr, flush=True)
+
+
 def read_traffic(kernel_key):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
     (FETCH_SIZE / WRITE_SIZE runs); None when no summary for this kernel and workload exists."""
@@ -157,6 +162,7 @@ def measure(args, ew, synth, torch, w, starts, A, keep_state, steps=None, warmup
     old_after = {a: [t if alive[j] else None for j, t in enumerate(old[a])] for a in A}
     snap_used = {a: [None if alive[j] else t for j, t in enumerate(snap[a])] for a in A}
     torch.cuda.synchronize()
+    log(f"{w.name} arrays {','.join(A)}: state resident in HBM")
 
     numel = w.numel
     n_remote = stage_len
@@ -245,6 +251,7 @@ def measure(args, ew, synth, torch, w, starts, A, keep_state, steps=None, warmup
 
     # ---------------- the timed region (inside run_path): exactly K steps of the headline path
     head = run_path(args.unfused, steps, warmup)
+    log(f"{w.name} arrays {','.join(A)}: {steps} timed steps done, {head['ms_per_step']:.3f} ms per step")
     other = run_path(not args.unfused, steps, 1) if do_other else None
 
     # yardstick (outside the timed region): the library's plain copy kernel on one fp32 rank shard,
@@ -427,7 +434,7 @@ def compact(res):
            "frac_of_hbm_peak": round(h["value"] / HBM_PEAK_GBS, 4), "plan_ms": round(h["plan_ms"], 3),
            "reshard_one_stage_ms": round(res["reshard_only_ms"], 3),
            "reshard_without_arena_ms": round(res["direct_ms"], 3),
-           "kernel_GBps": {ph: k["GB/s"] for ph, k in h["kernels"].items()},
+           "kernel_GBps": {ph: k["GB/s"] for ph, k in h["kernels"].items() if k["GB"] > 0},
            "dominant_kernel": {"kernel": h["roofline"]["kernel"].split()[0], "GBps": h["roofline"]["achieved"],
                                "frac": h["roofline"]["frac"], "avg_launch_us": h["roofline"]["avg_launch_us"]}}
     if w.name == "70b_stage":
@@ -590,7 +597,9 @@ def main():
         s_old_len = o_lay.shard_lengths(s_starts, w.old_dp)
         host = {a: [synth.to_numpy_bits(old[a][j][:s_old_len[j]]) for j in range(w.old_dp)] for a in A}
         torch.cuda.synchronize()
+        log("CPU oracle baseline on one core ...")
         cpu_bytes, cpu_s = cpu_baseline(w, starts, host, n_units, 1)
+        log(f"CPU oracle baseline: {cpu_s:.1f} s")
         out["cpu_baseline"] = {
             "value": round(cpu_bytes / cpu_s / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
             "sample": f"first {n_units} of {len(starts) - 1} units of {w.name} ({s_numel} elements, all four arrays): "
@@ -624,6 +633,7 @@ def main():
                       "ms_per_step": round(t["head"]["ms_per_step"], 4), "plan_ms": round(t["head"]["plan_ms"], 4),
                       "reshard_one_stage_ms": round(t["reshard_only_ms"], 4), "device_part_latency": t["tiny_latency"]}
         del t
+        log("workloads: tiny done")
         r = rank_snapshot_measure(ew, configs, synth, torch, 10, 2)
         wl["7b_rank_snapshot"] = {"note": r["w"].note, "state_GB": round(14 * r["w"].numel / 1e9, 3),
                                   "ms_per_step": round(r["ms_per_step"], 4),
@@ -633,6 +643,7 @@ def main():
         for name, k in (("13b_stage", 5), ("70b_stage", 3)):
             t = run_stage(args, ew, configs, synth, torch, name, steps=k, warmup=1, do_other=False, extras=False)
             wl[name] = compact(t)
+            log(f"workloads: {name} done")
             del t
             torch.cuda.empty_cache()
         out["workloads"] = wl
