@@ -344,7 +344,8 @@ int ew_memcpy(const void *src, void *dst, uint64_t nbytes, void *stream);
  * (ew_snapshot uses one-wave workgroups from this size on, 256-lane ones below; default: never),
  * "snapshot_xcd_group_kib" (ew_snapshot's chunks go to the XCDs in runs of this many KiB; default 128),
  * "fused_wgs_per_cu", "verify_wgs_per_cu", "adam_wgs_per_cu" (workgroups resident per CU for the
- * kernels of ew_unpack_snapshot, ew_verify and ew_adam_step; 0 = all that fit; defaults 0, 4, 11),
+ * kernels of ew_unpack_snapshot, ew_verify and ew_adam_step; 0 = all that fit; defaults 0, 4, 12),
+ * "adam_xcd_group" (ew_adam_step's 256-element workgroups go to the XCDs in runs of this many; default 256),
  * "xcd_group_kib" (the tile kernels hand each of the 8 XCDs runs of consecutive tiles of this many
  * KiB instead of dealing tiles out one by one; 0 = one by one; default 2048),
  * "fused_mode" (0 = default; 1 forces the scratch-free form of ew_unpack_snapshot),

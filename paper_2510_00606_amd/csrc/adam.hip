@@ -77,8 +77,10 @@ __device__ __forceinline__ float load_grad(const void *g, uint64_t i) {
 template <int GES, bool VEC>
 __global__ __launch_bounds__(kThreads) void ew_adam_kernel(uint16_t *__restrict__ p, float *__restrict__ w,
                                                            float *__restrict__ m, float *__restrict__ v,
-                                                           const void *__restrict__ g, uint64_t n, ew_adam_t h) {
-  const uint64_t lane = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+                                                           const void *__restrict__ g, uint64_t n, ew_adam_t h,
+                                                           uint32_t xcd_group) {
+  // workgroups go to the XCDs in runs of consecutive 256-element chunks (see ew::xcd_remap)
+  const uint64_t lane = (VEC ? ew::xcd_remap(blockIdx.x, gridDim.x, xcd_group) : (uint64_t)blockIdx.x) * kThreads + threadIdx.x;
   if (VEC) {
     const uint64_t i = lane * 4;
     if (i + 4 <= n) {
@@ -201,17 +203,19 @@ int ew_adam_step(void *p_bf16, float *w, float *m, float *v, const void *grad, u
   if (grid > 0x7fffffffull) return EW_EINVAL;
   uint16_t *p = (uint16_t *)p_bf16;
   hipStream_t s = (hipStream_t)stream;
-  // Eight HBM streams per wave (four read, four written): with 11 one-wave workgroups resident per CU
+  // Eight HBM streams per wave (four read, four written): with 11-12 one-wave workgroups resident per CU
   // the step runs 7 % faster than with the 32 that fit (6.05 -> 6.52 TB/s measured in one process;
-  // 16: 6.34, 12: 6.48, 8: 6.03).
+  // 16: 6.34, 12: 6.48, 8: 6.03).  Runs of 256 consecutive workgroups per XCD add 1-1.5 % (6.44 -> 6.53
+  // TB/s at 12 per CU; runs of 16: 5.8-5.9, runs of 4096: 6.2).
   const uint32_t lds_pad = ew::occupancy_pad(ew::knobs().adam_wgs_per_cu, 0);
   const dim3 g((uint32_t)grid), b(kThreads);
+  const uint32_t xg = (uint32_t)ew::knobs().adam_xcd_group;  // in workgroups (256 elements each)
   if (grad_elem_size == 4) {
-    if (vec) hipLaunchKernelGGL((ew_adam_kernel<4, true>), g, b, lds_pad, s, p, w, m, v, grad, n, *h);
-    else hipLaunchKernelGGL((ew_adam_kernel<4, false>), g, b, lds_pad, s, p, w, m, v, grad, n, *h);
+    if (vec) hipLaunchKernelGGL((ew_adam_kernel<4, true>), g, b, lds_pad, s, p, w, m, v, grad, n, *h, xg);
+    else hipLaunchKernelGGL((ew_adam_kernel<4, false>), g, b, lds_pad, s, p, w, m, v, grad, n, *h, xg);
   } else {
-    if (vec) hipLaunchKernelGGL((ew_adam_kernel<2, true>), g, b, lds_pad, s, p, w, m, v, grad, n, *h);
-    else hipLaunchKernelGGL((ew_adam_kernel<2, false>), g, b, lds_pad, s, p, w, m, v, grad, n, *h);
+    if (vec) hipLaunchKernelGGL((ew_adam_kernel<2, true>), g, b, lds_pad, s, p, w, m, v, grad, n, *h, xg);
+    else hipLaunchKernelGGL((ew_adam_kernel<2, false>), g, b, lds_pad, s, p, w, m, v, grad, n, *h, xg);
   }
   EW_HIP(hipGetLastError());
   return EW_OK;

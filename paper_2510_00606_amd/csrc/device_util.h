@@ -22,7 +22,10 @@ __device__ __forceinline__ void store16(u32x4 *p, u32x4 v) { __builtin_nontempor
 // the instruction.  Measured on MI355X on the bare one-read-one-write and one-read-two-writes patterns
 // (one vector per lane, nontemporal loads), stores with sc1 set run 1.5-2 % and 2-3 % faster than
 // stores with nt alone (6.49 -> 6.61 and 6.08 -> 6.25 TB/s), and plain stores 3-5 % slower: sc1 makes
-// the write leave the L2 for memory at once instead of lingering there as a dirty line.
+// the write leave the L2 for memory at once instead of lingering there as a dirty line.  On the real
+// kernels (7B stage, one process, same buffers): snapshot +2 %, unpack +1 %, plain copy +1 %, fused
+// unpack + snapshot +1-1.5 %, pack -0.5 %; sc1 without nt, which is fine on the bare patterns, loses 6-8 %
+// on the tile kernels.
 // A window is wave-uniform: base and size live in scalar registers; lanes address it with a 32-bit
 // byte offset, and the hardware drops a store that falls outside [0, nbytes).
 #ifndef EW_STORE_AUX

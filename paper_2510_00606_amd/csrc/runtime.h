@@ -45,7 +45,8 @@ struct Knobs {
                                 // runs (with the identity mapping six per CU were 1-5 % faster than eight)
   Knob fused_mode{0};           // fused unpack + snapshot: 0 = slot per tile + fold kernel, 1 = scratch-free (atomics)
   Knob verify_wgs_per_cu{4};    // read-only streaming checksum (256 lanes; 8 fit)
-  Knob adam_wgs_per_cu{11};     // optimizer step (one wave per workgroup; 32 fit)
+  Knob adam_xcd_group{256};     // optimizer step: consecutive workgroups (256 elements each) per XCD; 1 = one by one
+  Knob adam_wgs_per_cu{12};     // optimizer step (one wave per workgroup; 32 fit)
 };
 Knobs &knobs();
 

@@ -306,6 +306,9 @@ int ew_set_param(const char *name, int64_t value) {
   } else if (!std::strcmp(name, "snapshot_xcd_group_kib")) {
     if (value < 0 || value > (1 << 20)) return EW_EINVAL;
     k.snapshot_xcd_group_kib = value;
+  } else if (!std::strcmp(name, "adam_xcd_group")) {
+    if (value < 1 || value > (1 << 24)) return EW_EINVAL;
+    k.adam_xcd_group = value;
   } else if (!std::strcmp(name, "xcd_group_kib")) {
     if (value < 0 || value > (1 << 20)) return EW_EINVAL;
     k.xcd_group_kib = value;
@@ -342,6 +345,7 @@ int64_t ew_get_param(const char *name) {
   if (!std::strcmp(name, "tile_align_bytes")) return k.tile_align_bytes;
   if (!std::strcmp(name, "fused_wgs_per_cu")) return k.fused_wgs_per_cu;
   if (!std::strcmp(name, "xcd_group_kib")) return k.xcd_group_kib;
+  if (!std::strcmp(name, "adam_xcd_group")) return k.adam_xcd_group;
   if (!std::strcmp(name, "snapshot_xcd_group_kib")) return k.snapshot_xcd_group_kib;
   if (!std::strcmp(name, "fused_mode")) return k.fused_mode;
   if (!std::strcmp(name, "verify_wgs_per_cu")) return k.verify_wgs_per_cu;

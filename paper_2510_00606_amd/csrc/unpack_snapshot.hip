@@ -17,12 +17,15 @@
 #include "device_util.h"
 #include "runtime.h"
 
-// cache policy of the store to the new shard and of the store to its snapshot copy (see StoreWindow)
+// Cache policy of the store to the new shard and of the store to its snapshot copy (see StoreWindow).
+// nt + sc1 on both, like the two-stream kernels: +1-1.5 % over nt alone now that tiles go to the XCDs
+// in runs (6.07 -> 6.12 and 5.98 -> 6.07 TB/s on two sets of buffers); with tiles dealt out one by one
+// it was neutral to -1 %, and giving the two stores different policies costs 1.5 % either way round.
 #ifndef EW_FUSED_AUX1
-#define EW_FUSED_AUX1 2
+#define EW_FUSED_AUX1 EW_STORE_AUX
 #endif
 #ifndef EW_FUSED_AUX2
-#define EW_FUSED_AUX2 2
+#define EW_FUSED_AUX2 EW_STORE_AUX
 #endif
 
 namespace {

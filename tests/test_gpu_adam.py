@@ -50,6 +50,20 @@ def test_device_step_is_bit_exact(n, shift, grad_bits):
     assert bool((pb[n:] == 0x5A5A).all()) and bool((wb[shift + n:] == 0).all()) and bool((wb[:shift] == 0).all())
 
 
+@pytest.mark.parametrize("group", [1, 3, 64, 256, 1 << 24])
+def test_device_step_with_workgroups_dealt_to_xcds_in_runs(group):
+    """Runs of consecutive chunks per XCD permute which workgroup updates which 256 elements, never the
+    result: run lengths that do not divide the launch, a ragged tail, runs longer than the launch."""
+    saved = ew.ew_get_param("adam_xcd_group")
+    ew.ew_set_param("adam_xcd_group", group)
+    try:
+        test_device_step_is_bit_exact(300_001, 0, 32)
+        test_device_step_is_bit_exact(1 << 21, 0, 16)
+        test_device_step_is_bit_exact(4099, 0, 32)
+    finally:
+        ew.ew_set_param("adam_xcd_group", saved)
+
+
 @pytest.mark.parametrize("wgs", [0, 1, 5, 12, 32])
 def test_device_step_with_occupancy_caps(wgs):
     """The cap on resident workgroups changes the launch only, never the result."""
