@@ -521,7 +521,8 @@ def test_enqueues_on_two_streams_overlap():
     threads meet in a given round is up to the scheduler), and the results are the oracle's."""
     import threading
     rng = np.random.default_rng(81)
-    nbytes = 5 * (1 << 30) // 2 + 4096 + 5     # 2.5 GiB: two passes over a region per call
+    ew.ew_set_param("snapshot_wave_min_bytes", 0)   # one slot per KiB: a region covers 2 GiB, so ...
+    nbytes = 5 * (1 << 30) // 2 + 4096 + 5     # ... 2.5 GiB takes two passes (four launches) per call
     raw8 = rng.integers(0, 1 << 62, 1 << 16, dtype=np.int64)
     src = torch.from_numpy(raw8).to(DEV).repeat((nbytes + 8 * len(raw8) - 1) // (8 * len(raw8))).view(torch.uint8)[:nbytes]
     dst = [torch.zeros(nbytes, dtype=torch.uint8, device=DEV) for _ in range(2)]
@@ -530,7 +531,7 @@ def test_enqueues_on_two_streams_overlap():
     torch.cuda.synchronize()
     errors = []
     seen = 0
-    for attempt in range(5):
+    for attempt in range(12):
         ew.ew_set_param("scratch_max_concurrent", 0)
         go = threading.Barrier(2)
 
