@@ -174,7 +174,12 @@ __global__ __launch_bounds__(kThreads) void ew_zero_records_kernel(SnapTabs st) 
 template <int ES>
 int launch_pass(const ew::TileTable &tt, uint64_t t0, uint64_t n, const CopyTabs &tabs, const SnapTabs &st,
                 ew_cksum_t *slots, hipStream_t stream) {
-  constexpr uint32_t kTilesPerLane = 16;
+  // Tiles per lane of the fold (knob fold_tiles_per_lane overrides).  Every run of equal (rank, block) costs a
+  // lane one pair of atomics, and those are what the kernel waits for: measured on a pass of 1.76 M tiles,
+  // 1 / 2 / 4 / 8 / 16 / 32 tiles per lane take 366 / 171 / 81 / 53 / 39 / 43 us; on a pass of 1024 tiles
+  // 19 / 12 / 10 / 11 / 12 / 18 us.
+  const int64_t knob = ew::knobs().fold_tiles_per_lane;
+  const uint32_t kTilesPerLane = knob > 0 ? (uint32_t)knob : (n < 65536 ? 4u : 16u);
   const uint64_t fold_grid = ((n + kTilesPerLane - 1) / kTilesPerLane + kThreads - 1) / kThreads;
   // Resident workgroups per CU can be capped by asking for unused dynamic LDS (knob fused_wgs_per_cu).
   // With tiles dealt to the XCDs one by one, six per CU were 1-5 % faster than the eight that fit

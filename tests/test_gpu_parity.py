@@ -18,7 +18,8 @@ MIB = 1 << 20
 def default_params():
     saved = {k: ew.ew_get_param(k) for k in ("tile_bytes", "tile_elems", "tile_align_bytes", "cksum_sub_bytes", "cksum_wgs_per_cu",
                                               "cksum_mode", "fused_wgs_per_cu", "fused_mode", "verify_wgs_per_cu",
-                                              "snapshot_wave_min_bytes", "xcd_group_kib", "snapshot_xcd_group_kib")}
+                                              "snapshot_wave_min_bytes", "xcd_group_kib", "snapshot_xcd_group_kib",
+                                              "fold_tiles_per_lane")}
     yield
     for k, v in saved.items():
         ew.ew_set_param(k, v)
@@ -353,6 +354,18 @@ def test_tiles_dealt_to_xcds_in_runs(kib):
         reshard_case(3, 2, 0b111, 2_600_000, 99_992, es, rng)
         reshard_case(6, 4, 0b111011, 999_999, 10_007, es, rng, tile_elems=1000)
         reshard_case(4, 3, 0b1011, 4099, 264, es, rng)
+
+
+@pytest.mark.parametrize("per_lane", [1, 3, 16, 1000])
+def test_fused_fold_with_any_number_of_tiles_per_lane(per_lane):
+    """How many tiles a lane of the fold kernel walks changes how the slots meet in the records, never the
+    records: one tile per lane, counts that do not divide a block's tiles, more tiles per lane than a pass has."""
+    ew.ew_set_param("fold_tiles_per_lane", per_lane)
+    rng = np.random.default_rng(700 + per_lane)
+    for es in (2, 4):
+        reshard_case(8, 7, 0xFF & ~(1 << 5), 3_000_000 + 8 * 37, 262144, es, rng)
+        reshard_case(3, 2, 0b111, 2_600_000, 99_992, es, rng)
+        reshard_case(2, 3, 0b10, 1_900_003, 70_001, es, rng)
 
 
 def test_fused_unpack_scratch_free_form():
