@@ -43,7 +43,7 @@ struct Knobs {
   // fewer requests in flight.
   Knob fused_wgs_per_cu{0};     // fused unpack + snapshot (256 lanes; 8 fit): no cap since tiles go to XCDs in
                                 // runs (with the identity mapping six per CU were 1-5 % faster than eight)
-  Knob fold_tiles_per_lane{0};  // fused unpack + snapshot: tiles per lane of the fold kernel (0 = by pass size)
+  Knob fold_tiles_per_lane{0};  // fused unpack + snapshot: tiles per lane of the fold kernel (0 = default)
   Knob fused_mode{0};           // fused unpack + snapshot: 0 = slot per tile + fold kernel, 1 = scratch-free (atomics)
   Knob verify_wgs_per_cu{4};    // read-only streaming checksum (256 lanes; 8 fit)
   Knob adam_xcd_group{256};     // optimizer step: consecutive workgroups (256 elements each) per XCD; 1 = one by one

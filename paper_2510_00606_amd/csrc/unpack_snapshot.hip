@@ -133,16 +133,20 @@ __global__ __launch_bounds__(kThreads) void ew_unpack_snap_kernel(TableRef table
   }
 }
 
-// Lane g adds the slots of tiles [g*per_lane, (g+1)*per_lane) of the pass to the records, one
-// pair of atomics per run of tiles that share (new rank, block): tiles of a segment are adjacent.
+// Lane g walks the slots of tiles [g*per_lane, (g+1)*per_lane) of the pass and sums runs of tiles that share
+// (new rank, block): tiles of a segment are adjacent, and tiles are numbered destination-major, so the keys
+// never decrease along the lanes.  A run that ends inside a lane's range goes to its record at once; the
+// run still open at the end of the range is first combined with the equal-keyed open runs of the following
+// lanes of the wave (a segmented reduction with shuffles), and only the first lane of every key adds it to
+// the record: one pair of atomics per (wave, block) instead of one per lane -- the atomics are what this
+// kernel waits for.
 template <int ES>
 __global__ __launch_bounds__(kThreads) void ew_fold_tiles_kernel(TableRef table, uint64_t tile_base, uint64_t ntiles,
                                                                  uint32_t per_lane, SnapTabs st,
                                                                  const ew_cksum_t *__restrict__ slots) {
   const uint64_t g = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
-  uint64_t i = g * per_lane;
+  uint64_t i = g * per_lane;  // may lie beyond the pass: such lanes only take part in the shuffles
   const uint64_t end = (i + per_lane < ntiles) ? i + per_lane : ntiles;
-  if (i >= end) return;
   uint32_t key_rank = 0;
   uint64_t key_blk = 0, sum = 0, xr = 0;
   bool open = false;
@@ -161,7 +165,21 @@ __global__ __launch_bounds__(kThreads) void ew_fold_tiles_kernel(TableRef table,
     sum += r.sum;
     xr ^= r.xr;
   }
-  add_to_record(st.rec[key_rank] + key_blk, sum, xr);
+  // block numbers stay below 2^44 (byte offsets below 2^64), ranks below 2^7
+  const uint64_t none = ~(uint64_t)0;
+  const uint64_t key = open ? (((uint64_t)key_rank << 44) | key_blk) : none;
+  const int lane = threadIdx.x & 63;
+  for (int d = 1; d < 64; d <<= 1) {
+    const uint64_t other_key = __shfl_down((unsigned long long)key, d, 64);
+    const uint64_t other_sum = __shfl_down((unsigned long long)sum, d, 64);
+    const uint64_t other_xr = __shfl_down((unsigned long long)xr, d, 64);
+    if (lane + d < 64 && other_key == key) {  // equal keys are contiguous: lane + d lies in the same run
+      sum += other_sum;
+      xr ^= other_xr;
+    }
+  }
+  const uint64_t prev_key = __shfl_up((unsigned long long)key, 1, 64);
+  if (open && (lane == 0 || prev_key != key)) add_to_record(st.rec[key_rank] + key_blk, sum, xr);
 }
 
 // Zeroes every new rank's records: blockIdx.y = rank, 2 words per record.
@@ -174,12 +192,13 @@ __global__ __launch_bounds__(kThreads) void ew_zero_records_kernel(SnapTabs st) 
 template <int ES>
 int launch_pass(const ew::TileTable &tt, uint64_t t0, uint64_t n, const CopyTabs &tabs, const SnapTabs &st,
                 ew_cksum_t *slots, hipStream_t stream) {
-  // Tiles per lane of the fold (knob fold_tiles_per_lane overrides).  Every run of equal (rank, block) costs a
-  // lane one pair of atomics, and those are what the kernel waits for: measured on a pass of 1.76 M tiles,
-  // 1 / 2 / 4 / 8 / 16 / 32 tiles per lane take 366 / 171 / 81 / 53 / 39 / 43 us; on a pass of 1024 tiles
-  // 19 / 12 / 10 / 11 / 12 / 18 us.
+  // Tiles per lane of the fold (knob fold_tiles_per_lane overrides).  With the lanes' open runs combined
+  // across the wave before anything is added to a record, few tiles per lane are best: 1 / 2 / 4 / 8 / 16 / 32
+  // per lane take 16.6 / 15.8 / 17.4 / 24.6 / 30.1 / 40.6 us on a pass of 1.76 M tiles and 3.6 / 3.8 / 4.9 /
+  // 7.9 / 10.7 / 18.4 us on one of 1024 tiles (one pair of atomics per lane, as before: 366 / 171 / 81 / 53 /
+  // 39 / 43 and 19 / 12 / 10 / 11 / 12 / 18 us).
   const int64_t knob = ew::knobs().fold_tiles_per_lane;
-  const uint32_t kTilesPerLane = knob > 0 ? (uint32_t)knob : (n < 65536 ? 4u : 16u);
+  const uint32_t kTilesPerLane = knob > 0 ? (uint32_t)knob : 2u;
   const uint64_t fold_grid = ((n + kTilesPerLane - 1) / kTilesPerLane + kThreads - 1) / kThreads;
   // Resident workgroups per CU can be capped by asking for unused dynamic LDS (knob fused_wgs_per_cu).
   // With tiles dealt to the XCDs one by one, six per CU were 1-5 % faster than the eight that fit
