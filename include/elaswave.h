@@ -268,7 +268,7 @@ int ew_scratch_release(void *stream);
  * For code under HIP graph capture, tight serving loops and harnesses that forbid allocation: same
  * arguments and results as ew_snapshot, but the call touches no allocator of any kind -- no
  * hipMalloc / hipFree, no event or lock creation, no scratch lease.  Its checksum slots live in a
- * second fixed device array of 16 MiB (one 16-byte slot per KiB of input) that every GPU the
+ * second fixed device array of 16 MiB (sized for one 16-byte slot per KiB of input) that every GPU the
  * library runs on holds until the process ends; the array's address is looked up on the first call
  * on each device (make that call outside a capture).
  * nbytes above EW_NOALLOC_MAX_BYTES (1 GiB: more than one fp32 array of a 7B-stage rank shard)
