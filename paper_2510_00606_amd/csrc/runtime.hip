@@ -189,6 +189,9 @@ ScratchLease::ScratchLease(hipStream_t stream) : stream_(stream) {
       if ((int)r != pick && !reg[r].in_graph) ++others_free;
     if (others_free == 0) return;
   }
+  // marked here, under the lock that the test above ran under, so two captures that start at the same
+  // time cannot both take a "last but one" region; the graph's own ordering covers its replays
+  if (capturing_) reg[pick].in_graph = true;
   reg[pick].taken = true;
   reg[pick].busy = true;
   reg[pick].owner = stream;
@@ -224,9 +227,7 @@ ScratchLease::~ScratchLease() {
   {
     std::lock_guard<std::mutex> lock(dev_->mu);
     r->last_use = ++dev_->clock;
-    if (capturing_) {
-      r->in_graph = true;  // the graph's own ordering covers its replays on one stream
-    } else {
+    if (!capturing_) {
       r->done = ev;
       r->recorded = recorded;
     }
