@@ -380,6 +380,82 @@ def test_fused_unpack_scratch_free_form():
         reshard_case(4, 3, 0b1011, 4099, 264, es, rng)
 
 
+# ------------------------------------------------------------------ a run of failures and joins
+@pytest.mark.parametrize("elem_size", [2, 4])
+def test_chain_of_failures_and_joins(elem_size):
+    """Sec. 5.1 + 5.2 over several events: what the fused unpack leaves behind (new shards, their
+    snapshot copies, their checksums) is what the next event recovers from.  After every event the
+    new shards are the oracle's slices of the one flat array that never changes, the snapshot copies
+    equal them, the checksums are the oracle's, and the snapshot a recovery is about to read
+    verifies clean -- once after a planted bit flip was found and undone."""
+    rng = np.random.default_rng(700 + elem_size)
+    cuts = np.unique(np.concatenate([[0], rng.integers(1, 900_000, 37) * 8, [900_000 * 8 + 8 * 13]]))
+    starts = cuts.astype(np.int64)
+    npdt = {2: np.uint16, 4: np.uint32}[elem_size]
+    flat = rng.integers(0, 1 << (8 * elem_size), size=int(starts[-1]), dtype=np.uint64).astype(npdt)
+    dp = 8
+    want = layout.slice_flat(flat, dp, starts)
+    shards = [to_dev(a, elem_size) for a in want]
+    snaps, cks = [], []
+    for a, t in zip(want, shards):          # the first snapshots come from ew_snapshot
+        sn = torch.empty_like(t)
+        ck = torch.zeros((ew.num_blocks(a.nbytes), 2), dtype=torch.int64, device=DEV)
+        ew.ew_snapshot(t, sn, a.nbytes, ck, stream())
+        snaps.append(sn)
+        cks.append(ck)
+    events = [(7, [5]), (8, []), (6, [1, 4]), (4, [0, 2]), (5, [3]), (5, [1, 3]), (1, [0, 2]), (3, [])]
+    poison = 0xDEAD if elem_size == 2 else 0xDEADBEEF
+    for step, (new_dp, failed) in enumerate(events):
+        mask = sum(1 << j for j in range(dp) if j not in failed)
+        for j in failed:
+            shards[j].fill_(poison - (1 << (8 * elem_size)))     # the live shard is gone
+            nbytes = want[j].nbytes
+            nb = ew.num_blocks(nbytes)
+            got = torch.zeros((nb, 2), dtype=torch.int64, device=DEV)
+            n_bad = torch.zeros(1, dtype=torch.int64, device=DEV)
+            bad = torch.full((4,), -1, dtype=torch.int64, device=DEV)
+            diffs = torch.zeros((4, 2), dtype=torch.int64, device=DEV)
+            if step == 2 and j == failed[0]:      # a flipped bit in the snapshot is found, then undone
+                o, bit = int(rng.integers(0, nbytes)), int(rng.integers(0, 8))
+                raw = snaps[j].view(torch.uint8)
+                raw[o] ^= (1 << bit)
+                ew.ew_verify(snaps[j], nbytes, cks[j], got, n_bad, bad, diffs, 4, stream())
+                torch.cuda.synchronize()
+                assert int(n_bad.item()) == 1 and int(bad[0].item()) == o >> 20
+                d = diffs.cpu().numpy().view(np.uint64)[0]
+                lane, direction = ew.ew_single_bit_flip(int(d[0]), int(d[1]))
+                assert lane == 8 * (o % 8) + bit
+                raw[o] ^= (1 << bit)
+            ew.ew_verify(snaps[j], nbytes, cks[j], got, n_bad, bad, diffs, 4, stream())
+            torch.cuda.synchronize()
+            assert int(n_bad.item()) == 0, f"event {step}: snapshot of rank {j} does not verify"
+        plan = ew.ew_plan_bounds(dp, new_dp, mask, starts)
+        ew.ew_plan_upload(plan, 0, stream())
+        stage = guarded(plan.stage_len, elem_size)
+        alive_snaps = [snaps[j] if j in failed else None for j in range(dp)]
+        ew.ew_pack(plan, shards, alive_snaps, stage, elem_size, stream())
+        lens = [plan.new_shard_len(k) for k in range(new_dp)]
+        new = [guarded(n, elem_size) for n in lens]
+        new_snaps = [guarded(n, elem_size) for n in lens]
+        new_cks = [torch.full((ew.num_blocks(n * elem_size) + 1, 2), -1, dtype=torch.int64, device=DEV) for n in lens]
+        ew.ew_unpack_snapshot(plan, stage, shards, alive_snaps, new, new_snaps, new_cks, elem_size, stream())
+        torch.cuda.synchronize()
+        plan.close()
+        want = layout.slice_flat(flat, new_dp, starts)
+        for k in range(new_dp):
+            n = lens[k]
+            assert n == len(want[k])
+            assert np.array_equal(np_bits(new[k][:n]), want[k]), f"event {step}: new shard {k} differs"
+            assert np.array_equal(np_bits(new_snaps[k][:n]), want[k]), f"event {step}: snapshot {k} differs"
+            assert guard_intact(new[k], n, elem_size) and guard_intact(new_snaps[k], n, elem_size)
+            nb = ew.num_blocks(n * elem_size)
+            assert np.array_equal(new_cks[k].cpu().numpy().view(np.uint64)[:nb], checksum.block_checksums(want[k]))
+        shards = [t[:n] for t, n in zip(new, lens)]
+        snaps = [t[:n] for t, n in zip(new_snaps, lens)]
+        cks = [t[:ew.num_blocks(n * elem_size)] for t, n in zip(new_cks, lens)]
+        dp = new_dp
+
+
 def test_null_buffers_are_rejected():
     plan = ew.ew_plan(4, 3, 0b1011, 1 << 16, 4096)
     ew.ew_plan_upload(plan, 0, stream())
