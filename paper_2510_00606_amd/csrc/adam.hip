@@ -78,9 +78,9 @@ template <int GES, bool VEC>
 __global__ __launch_bounds__(kThreads) void ew_adam_kernel(uint16_t *__restrict__ p, float *__restrict__ w,
                                                            float *__restrict__ m, float *__restrict__ v,
                                                            const void *__restrict__ g, uint64_t n, ew_adam_t h,
-                                                           uint32_t xcd_group) {
+                                                           ew::XcdMap xcd) {
   // workgroups go to the XCDs in runs of consecutive 256-element chunks (see ew::xcd_remap)
-  const uint64_t lane = (VEC ? ew::xcd_remap(blockIdx.x, gridDim.x, xcd_group) : (uint64_t)blockIdx.x) * kThreads + threadIdx.x;
+  const uint64_t lane = (uint64_t)(VEC ? ew::xcd_remap(blockIdx.x, xcd) : blockIdx.x) * kThreads + threadIdx.x;
   if (VEC) {
     const uint64_t i = lane * 4;
     if (i + 4 <= n) {
@@ -209,7 +209,7 @@ int ew_adam_step(void *p_bf16, float *w, float *m, float *v, const void *grad, u
   // TB/s at 12 per CU; runs of 16: 5.8-5.9, runs of 4096: 6.2).
   const uint32_t lds_pad = ew::occupancy_pad(ew::knobs().adam_wgs_per_cu, 0);
   const dim3 g((uint32_t)grid), b(kThreads);
-  const uint32_t xg = (uint32_t)ew::knobs().adam_xcd_group;  // in workgroups (256 elements each)
+  const ew::XcdMap xg = ew::make_xcd_map((uint32_t)ew::knobs().adam_xcd_group, (uint32_t)grid);  // in workgroups (256 elements each)
   if (grad_elem_size == 4) {
     if (vec) hipLaunchKernelGGL((ew_adam_kernel<4, true>), g, b, lds_pad, s, p, w, m, v, grad, n, *h, xg);
     else hipLaunchKernelGGL((ew_adam_kernel<4, false>), g, b, lds_pad, s, p, w, m, v, grad, n, *h, xg);

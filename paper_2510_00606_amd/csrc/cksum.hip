@@ -116,9 +116,9 @@ __global__ __launch_bounds__(kThreads) void ew_cksum_kernel(const char *__restri
 template <bool COPY, int WAVES>
 __global__ __launch_bounds__(64 * WAVES) void ew_cksum_slots_kernel(const u32x4 *__restrict__ src,
                                                                     u32x4 *__restrict__ dst, uint64_t nbytes,
-                                                                    ew_cksum_t *__restrict__ slots, uint32_t xcd_group) {
+                                                                    ew_cksum_t *__restrict__ slots, ew::XcdMap xcd) {
   static_assert(WAVES == 1 || 64 * WAVES == kThreads, "block_fold is written for kThreads lanes");
-  const uint64_t chunk = ew::xcd_remap(blockIdx.x, gridDim.x, xcd_group);  // which WAVES KiB of the buffer
+  const uint64_t chunk = ew::xcd_remap(blockIdx.x, xcd);  // which WAVES KiB of the buffer
   const uint64_t first = chunk * (64 * WAVES);  // the workgroup's first vector
   const uint64_t i = first + threadIdx.x;
   const uint64_t nvec = nbytes >> 4;
@@ -277,10 +277,10 @@ int launch_cksum_slots(const void *src, void *dst, uint64_t nbytes, ew_cksum_t *
     u32x4 *d = (u32x4 *)(COPY ? (char *)dst + off : nullptr);
     if (one_wave)
       hipLaunchKernelGGL((ew_cksum_slots_kernel<COPY, 1>), dim3((uint32_t)grid), dim3(64), 0, stream, s, d, n, slots,
-                         xcd_group);
+                         ew::make_xcd_map(xcd_group, (uint32_t)grid));
     else
       hipLaunchKernelGGL((ew_cksum_slots_kernel<COPY, 4>), dim3((uint32_t)grid), dim3(256), 0, stream, s, d, n, slots,
-                         xcd_group);
+                         ew::make_xcd_map(xcd_group, (uint32_t)grid));
     EW_HIP(hipGetLastError());
     hipLaunchKernelGGL(ew_fold_kernel, dim3((uint32_t)nblk), dim3(kThreads), 0, stream, slots, grid,
                        (uint32_t)(EW_CKSUM_BLOCK / slot_bytes), out + off / EW_CKSUM_BLOCK);

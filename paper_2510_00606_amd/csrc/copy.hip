@@ -23,19 +23,26 @@ using ew::u32x4;
 // One workgroup copies one tile: at most tile_elems elements of one segment of one unit, i.e. a
 // plain contiguous copy between two buffers picked from the pointer tables.  The tile id is
 // decoded against the run-length tables: record (one coarse-index lookup plus a short walk), unit
-// inside the record (one division), tile template inside the unit.  Everything up to the addresses
-// is wave-uniform and runs on the scalar unit from cache-resident tables, so no per-tile record is
-// streamed from HBM.  The default tile is 4 KiB: every lane moves one 128-bit vector, and the GPU
-// is kept full by the sheer number of workgroups.
+// inside the record (a multiply and two shifts prepared per record), tile template inside the unit.
+// Everything up to the addresses is wave-uniform and runs on the scalar unit from cache-resident
+// tables, so no per-tile record is streamed from HBM: about 95 scalar instructions and five round
+// trips to the scalar cache (arguments, coarse index, record, template, the two buffer pointers) before
+// the workgroup's vector load.  With a true division in the decode and in the workgroup -> tile mapping,
+// member-wise reads of the record and one round trip per pointer it was 190 instructions, some on the
+// vector unit, and nine round trips, and pack and unpack ran 1.3-1.5 % slower.  The default tile is
+// 4 KiB: every lane moves one 128-bit vector, and the GPU is kept full by the sheer number of workgroups.
 //
 // There is no loop over tiles: every table load then precedes every store of the workgroup, which
 // lets the compiler keep the decode on the scalar unit (a persistent loop forces vector loads of
 // the tables, since a store might alias them: 3.9 instead of 6.2 TB/s).
 template <int ES>
-__global__ __launch_bounds__(kThreads) void ew_segcopy_kernel(TableRef table, CopyTabs tabs, uint32_t xcd_group) {
-  const ew::TileRef tl = ew::decode_tile(table, ew::xcd_remap(blockIdx.x, gridDim.x, xcd_group));
-  const char *s = tabs.src[tl.src_buf] + tl.src_off * ES;
-  char *d = tabs.dst[tl.dst_buf] + tl.dst_off * ES;
+__global__ __launch_bounds__(kThreads) void ew_segcopy_kernel(TableRef table, CopyTabs tabs, ew::XcdMap xcd) {
+  const ew::TileRef tl = ew::decode_tile(table, ew::xcd_remap(blockIdx.x, xcd));
+  const char *sbase = tabs.src[tl.src_buf];
+  char *dbase = tabs.dst[tl.dst_buf];
+  ew::want_scalars((uint64_t)sbase, (uint64_t)dbase);
+  const char *s = sbase + tl.src_off * ES;
+  char *d = dbase + tl.dst_off * ES;
   const uint32_t nbytes = tl.len * ES;
   if ((((uintptr_t)s | (uintptr_t)d) & 15u) == 0) {
     const u32x4 *sv = reinterpret_cast<const u32x4 *>(s);
@@ -99,7 +106,7 @@ void release_tables(ew_plan_t *plan) {
 int launch_segcopy(const ew::TileTable &tt, const CopyTabs &tabs, uint32_t elem_size, hipStream_t stream) {
   if (tt.ntiles == 0) return EW_OK;
   const uint32_t grid = (uint32_t)tt.ntiles;  // ew_plan_upload refuses tables above 2^31-1 tiles
-  const uint32_t g = ew::xcd_group_for((uint64_t)tt.tile_bytes);
+  const ew::XcdMap g = ew::make_xcd_map(ew::xcd_group_for((uint64_t)tt.tile_bytes), grid);
   if (elem_size == 2)
     hipLaunchKernelGGL(ew_segcopy_kernel<2>, dim3(grid), dim3(kThreads), 0, stream, tt.dev, tabs, g);
   else

@@ -56,9 +56,9 @@ __device__ __forceinline__ void fold(u32x4 v, uint64_t &sum, uint64_t &xr) {
 // workgroup's run time.)
 template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ uint64_t dpp_mov64(uint64_t v) {
-  const uint32_t lo = __builtin_amdgcn_update_dpp(0u, (uint32_t)v, CTRL, ROW_MASK, 0xf, false);
-  const uint32_t hi = __builtin_amdgcn_update_dpp(0u, (uint32_t)(v >> 32), CTRL, ROW_MASK, 0xf, false);
-  return (uint64_t)lo | ((uint64_t)hi << 32);
+  // the 64-bit form moves the two halves as a register pair (built from two 32-bit moves and an or,
+  // the sum of the pair cost two 64-bit additions per step)
+  return __builtin_amdgcn_update_dpp((uint64_t)0, v, CTRL, ROW_MASK, 0xf, false);
 }
 constexpr int kWaveFoldLane = 63;
 __device__ __forceinline__ void wave_fold(uint64_t &sum, uint64_t &xr) {
@@ -96,6 +96,22 @@ __device__ __forceinline__ void block_fold(uint64_t &sum, uint64_t &xr, uint64_t
       xr ^= lds_xor[w];
     }
   }
+}
+
+// Wave-uniform values wanted in scalar registers at this point of the program: the scalar loads that
+// produce them (here: entries of the pointer tables in the kernel arguments) are then issued together and
+// waited for once, instead of one round trip to the scalar cache each at their first use.  A workgroup
+// of the tile kernels lives for a few microseconds around one vector load, and what precedes that load
+// shows in the rate.  Only for use AFTER a kernel's last table load: the compiler takes the statement for
+// something that may write memory, and scalar loads of global memory behind it become vector loads.
+// (Pointers go in as integers; the pointers themselves keep their address space.)
+template <class T0, class T1>
+__device__ __forceinline__ void want_scalars(T0 a, T1 b) {
+  asm volatile("" ::"s"(a), "s"(b));
+}
+template <class T0, class T1, class T2>
+__device__ __forceinline__ void want_scalars(T0 a, T1 b, T2 c) {
+  asm volatile("" ::"s"(a), "s"(b), "s"(c));
 }
 
 }  // namespace ew

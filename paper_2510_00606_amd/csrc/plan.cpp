@@ -347,6 +347,7 @@ void build_tile_table(const ew_plan_t &plan, int which, uint32_t tile_elems, uin
       rt.tiles_per_unit = (uint32_t)(out.templ.size() - rt.templ_begin);
       out.ntiles += (uint64_t)rt.tiles_per_unit * reps;
       rt.tile_end = out.ntiles;
+      div_invariant_setup(rt.tiles_per_unit, rt.div_magic, rt.div_sh1, rt.div_sh2);
       rt.pad = 0;
       out.runs.push_back(rt);
     };
@@ -523,7 +524,9 @@ uint64_t ew_plan_pair_off(const ew_plan_t *p, uint32_t h, uint32_t k) {
 }
 
 uint64_t ew_tile_of_workgroup(uint64_t workgroup, uint64_t n_workgroups, uint32_t group) {
-  return ew::xcd_remap(workgroup, n_workgroups, group);
+  // launches have fewer than 2^31 workgroups; beyond that nothing is remapped
+  if (workgroup >= n_workgroups || n_workgroups > 0x7fffffffull) return workgroup;
+  return ew::xcd_remap((uint32_t)workgroup, ew::make_xcd_map(group, (uint32_t)n_workgroups));
 }
 
 }  // extern "C"

@@ -50,7 +50,9 @@ struct RunT {
   uint64_t tile_end;        // one past its last tile (= the next record's tile_begin)
   uint32_t tiles_per_unit;  // templates per repetition (> 0)
   uint32_t templ_begin;     // index of the record's first template
-  uint64_t pad;
+  uint32_t div_magic;       // n / tiles_per_unit for 32-bit n without a division: see div_by_invariant
+  uint8_t div_sh1, div_sh2;
+  uint16_t pad;
 };
 static_assert(sizeof(RunT) == 32, "run record must stay 32 bytes (one aligned scalar load)");
 
@@ -86,13 +88,52 @@ struct TableRef {
   uint32_t shift;
 };
 
-EW_HD TileRef decode_tile(const TableRef &tb, uint64_t t) {
-  uint32_t r = tb.coarse[t >> tb.shift];
-  RunT run = tb.runs[r];
-  while (t >= run.tile_end) run = tb.runs[++r];  // usually no step: the index lands on the record
+// Division of a 32-bit n by a divisor d >= 1 fixed in advance (Granlund and Montgomery, "Division by
+// invariant integers using multiplication", 1994): with l = ceil(log2 d),
+//   magic = floor(2^32 (2^l - d) / d) + 1,  sh1 = min(l, 1),  sh2 = l - sh1,
+//   t = high half of n * magic,  n / d = (t + ((n - t) >> sh1)) >> sh2   exactly, for every n < 2^32.
+// Five scalar instructions in a kernel, where a division costs forty and a trip through the vector unit.
+inline void div_invariant_setup(uint32_t d, uint32_t &magic, uint8_t &sh1, uint8_t &sh2) {
+  uint32_t l = 0;
+  while (l < 32 && ((uint64_t)1 << l) < d) ++l;
+  magic = (uint32_t)(((((uint64_t)1 << l) - d) << 32) / d + 1);
+  sh1 = (uint8_t)(l < 1 ? l : 1);
+  sh2 = (uint8_t)(l - sh1);
+}
+EW_HD uint32_t div_by_invariant(uint32_t n, uint32_t magic, uint32_t sh1, uint32_t sh2) {
+  const uint32_t t = (uint32_t)(((uint64_t)n * magic) >> 32);
+  return (t + ((n - t) >> sh1)) >> sh2;
+}
 
-  const uint64_t local = t - run.tile_begin;
-  const uint64_t unit = local / run.tiles_per_unit;
+// A record read as one 32-byte access (in a kernel: one scalar load and one wait, where member-wise
+// reads inside the search loop below turn into three dependent loads).
+EW_HD RunT load_run(const RunT *p) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  typedef uint32_t u32x8 __attribute__((ext_vector_type(8), aligned(16)));
+  const u32x8 raw = *reinterpret_cast<const u32x8 *>(p);
+  RunT r;
+  __builtin_memcpy(&r, &raw, sizeof(r));
+  return r;
+#else
+  return *p;
+#endif
+}
+
+EW_HD TileRef decode_tile(const TableRef &tb, uint64_t tile) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  typedef uint32_t tid_t;  // a table that a kernel reads holds fewer than 2^31 tiles (ew_plan_upload)
+#else
+  typedef uint64_t tid_t;  // the host may decode larger ones
+#endif
+  const tid_t t = (tid_t)tile;
+  uint32_t r = tb.coarse[t >> tb.shift];
+  RunT run = load_run(tb.runs + r);
+  while (t >= (tid_t)run.tile_end) run = load_run(tb.runs + ++r);  // usually no step: the index lands on the record
+
+  const tid_t local = t - (tid_t)run.tile_begin;
+  const uint64_t unit = ((uint64_t)local >> 32) == 0
+                            ? (uint64_t)div_by_invariant((uint32_t)local, run.div_magic, run.div_sh1, run.div_sh2)
+                            : (uint64_t)local / run.tiles_per_unit;
   const TileT tl = tb.templ[run.templ_begin + (uint32_t)(local - unit * run.tiles_per_unit)];
   TileRef ref;
   ref.src_off = tl.src_off + unit * tl.src_stride;
@@ -109,12 +150,29 @@ EW_HD TileRef decode_tile(const TableRef &tb, uint64_t t) {
 // relative to the destination-aligned cuts) is fetched from memory twice.  With group g > 1, inside
 // every block of 8*g consecutive workgroups XCD x takes the g consecutive tiles x*g .. x*g+g-1; the
 // launch as a whole still walks the tiles in order.  A trailing partial block keeps the identity.
-EW_HD uint64_t xcd_remap(uint64_t w, uint64_t n, uint32_t g) {
-  if (g <= 1) return w;
-  const uint64_t blk = 8ull * g, base = w / blk * blk;
-  if (base + blk > n) return w;
-  const uint64_t r = w - base;
-  return base + (r & 7) * g + (r >> 3);
+// The mapping is the first thing every workgroup computes, ahead of its only memory access, so a launch
+// gets it prepared: no branch and no division in the kernel (a dozen scalar instructions).
+struct XcdMap {
+  uint32_t g;      // >= 1; 1 is the identity
+  uint32_t n;      // workgroups of the launch (below 2^31)
+  uint32_t magic;  // division by 8 g, see div_by_invariant
+  uint8_t sh1, sh2;
+  uint16_t pad;
+};
+inline XcdMap make_xcd_map(uint32_t g, uint32_t n) {
+  XcdMap m;
+  m.g = g < 1 ? 1u : (g > (1u << 24) ? (1u << 24) : g);
+  m.n = n;
+  div_invariant_setup(8u * m.g, m.magic, m.sh1, m.sh2);
+  m.pad = 0;
+  return m;
+}
+EW_HD uint32_t xcd_remap(uint32_t w, const XcdMap &m) {
+  const uint32_t blk = 8u * m.g;
+  const uint32_t base = div_by_invariant(w, m.magic, m.sh1, m.sh2) * blk;
+  const uint32_t r = w - base;
+  const uint32_t t = base + (r & 7) * m.g + (r >> 3);
+  return base + blk <= m.n ? t : w;  // (base + blk stays below 2^31 + 2^27)
 }
 
 struct TileTable {       // host-side description of one (which, elem size) table

@@ -53,7 +53,7 @@ Knobs &knobs();
 
 int num_cus();
 
-// The group argument of xcd_remap for a kernel whose workgroups each cover unit_bytes of the
+// The group argument of make_xcd_map for a kernel whose workgroups each cover unit_bytes of the
 // destination (knob xcd_group_kib; 1 = identity).
 uint32_t xcd_group_for(uint64_t unit_bytes);
 

@@ -53,16 +53,19 @@ __device__ __forceinline__ void add_to_record(ew_cksum_t *rec, uint64_t sum, uin
 template <int ES, bool SLOTS>
 __global__ __launch_bounds__(kThreads) void ew_unpack_snap_kernel(TableRef table, uint64_t tile_base, CopyTabs tabs,
                                                                   SnapTabs st, ew_cksum_t *__restrict__ slots,
-                                                                  uint32_t xcd_group) {
+                                                                  ew::XcdMap xcd) {
   __shared__ uint64_t lds_sum[kThreads / 64], lds_xor[kThreads / 64];
   __shared__ uint64_t lds_sum_hi[kThreads / 64], lds_xor_hi[kThreads / 64];
   typedef typename std::conditional<ES == 2, uint16_t, uint32_t>::type elem_t;
-  const uint64_t tile = ew::xcd_remap(blockIdx.x, gridDim.x, xcd_group);  // of this pass
+  const uint32_t tile = ew::xcd_remap(blockIdx.x, xcd);  // of this pass
   const ew::TileRef tl = ew::decode_tile(table, tile_base + tile);
-  const char *s = tabs.src[tl.src_buf] + tl.src_off * ES;
+  const char *sbase = tabs.src[tl.src_buf];
+  char *dbase = tabs.dst[tl.dst_buf], *d2base = st.snap[tl.dst_buf];
+  ew::want_scalars((uint64_t)sbase, (uint64_t)dbase, (uint64_t)d2base);
+  const char *s = sbase + tl.src_off * ES;
   const uint64_t dbyte = tl.dst_off * ES;  // byte offset inside the new shard
-  char *d = tabs.dst[tl.dst_buf] + dbyte;
-  char *d2 = st.snap[tl.dst_buf] + dbyte;
+  char *d = dbase + dbyte;
+  char *d2 = d2base + dbyte;
   const uint32_t nbytes = tl.len * ES;
   const uint64_t boundary = ((dbyte >> 20) + 1) << 20;  // where the next checksum block starts
   const bool straddle = dbyte + nbytes > boundary;      // wave-uniform, rare
@@ -205,15 +208,15 @@ int launch_pass(const ew::TileTable &tt, uint64_t t0, uint64_t n, const CopyTabs
   // (three HBM streams per workgroup); with runs of tiles per XCD (xcd_remap) all eight are best
   // (7b stage, fp32: 5.97 / 5.98 / 5.85 / 5.62 TB/s at 8 / 7 / 6 / 5 per CU), so no cap by default.
   const uint32_t lds_pad = ew::occupancy_pad(ew::knobs().fused_wgs_per_cu, 8 * sizeof(uint64_t) * (kThreads / 64));
-  const uint32_t xcd_group = ew::xcd_group_for((uint64_t)tt.tile_bytes);
+  const ew::XcdMap xcd = ew::make_xcd_map(ew::xcd_group_for((uint64_t)tt.tile_bytes), (uint32_t)n);
   if (!slots) {  // no scratch region: the workgroups add to the records themselves
     hipLaunchKernelGGL((ew_unpack_snap_kernel<ES, false>), dim3((uint32_t)n), dim3(kThreads), lds_pad, stream, tt.dev,
-                       t0, tabs, st, slots, xcd_group);
+                       t0, tabs, st, slots, xcd);
     EW_HIP(hipGetLastError());
     return EW_OK;
   }
   hipLaunchKernelGGL((ew_unpack_snap_kernel<ES, true>), dim3((uint32_t)n), dim3(kThreads), lds_pad, stream, tt.dev, t0,
-                     tabs, st, slots, xcd_group);
+                     tabs, st, slots, xcd);
   EW_HIP(hipGetLastError());
   hipLaunchKernelGGL(ew_fold_tiles_kernel<ES>, dim3((uint32_t)fold_grid), dim3(kThreads), 0, stream, tt.dev, t0, n,
                      kTilesPerLane, st, slots);

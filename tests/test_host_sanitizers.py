@@ -38,7 +38,28 @@ DRIVER = textwrap.dedent(r"""
       ew_plan_free(p);
       return 0;
     }
+    // the multiply-and-shift division of the tile decoder against the machine's own, on every divisor
+    // up to 4096, divisors around every power of two, and dividends around multiples of the divisor
+    static int check_div() {
+      std::vector<uint32_t> ds;
+      for (uint32_t d = 1; d <= 4096; ++d) ds.push_back(d);
+      for (uint32_t b = 12; b < 32; ++b)
+        for (int o = -2; o <= 2; ++o) ds.push_back((uint32_t)((1ull << b) + o));
+      ds.push_back(0xffffffffu); ds.push_back(0xfffffffeu); ds.push_back(0x80000001u); ds.push_back(2654435761u);
+      uint64_t x = 88172645463325252ull;
+      for (uint32_t d : ds) {
+        uint32_t magic; uint8_t s1, s2;
+        ew::div_invariant_setup(d, magic, s1, s2);
+        std::vector<uint32_t> ns = {0u, 1u, d - 1, d, d + 1, 0x7fffffffu, 0x80000000u, 0xffffffffu, 0xfffffffeu};
+        for (unsigned long long k : {2ull, 3ull, 1000ull, 65535ull, 65536ull, (unsigned long long)(0xffffffffu / d)})
+          for (int o = -1; o <= 1; ++o) ns.push_back((uint32_t)(k * d + o));
+        for (int i = 0; i < 64; ++i) { x ^= x << 13; x ^= x >> 7; x ^= x << 17; ns.push_back((uint32_t)x); ns.push_back((uint32_t)(x >> 40)); }
+        for (uint32_t n : ns) REQUIRE(ew::div_by_invariant(n, magic, s1, s2) == n / d);
+      }
+      return 0;
+    }
     int main() {
+      if (check_div()) return 1;
       for (uint32_t Do = 1; Do <= 6; ++Do)
         for (uint32_t Dn = 1; Dn <= 6; ++Dn)
           for (uint64_t mask = 1; mask < (1ull << Do); ++mask)
