@@ -230,7 +230,9 @@ __global__ __launch_bounds__(kCmpThreads) void ew_compare_kernel(const ew_cksum_
 template <bool COPY>
 int launch_cksum_streaming(const void *src, void *dst, uint64_t nbytes, ew_cksum_t *out, hipStream_t stream) {
   const ew::Knobs &k = ew::knobs();
-  const uint32_t sub = (uint32_t)k.cksum_sub_bytes;
+  // A read-only pass over a large buffer runs as fewer, longer streams (see Knobs::verify_large_*).
+  const bool large = !COPY && nbytes >= (uint64_t)k.verify_large_min_bytes;
+  const uint32_t sub = (uint32_t)(large ? k.verify_large_sub_bytes : k.cksum_sub_bytes);
   const uint64_t nblocks = (nbytes + EW_CKSUM_BLOCK - 1) / EW_CKSUM_BLOCK;
   const uint32_t accumulate = sub < EW_CKSUM_BLOCK ? 1u : 0u;
   if (accumulate) {
@@ -244,9 +246,11 @@ int launch_cksum_streaming(const void *src, void *dst, uint64_t nbytes, ew_cksum
   }
   if (grid > 0x7fffffffull) grid = 0x7fffffffull;  // the kernel strides over what is left
   const bool aligned = ((((uintptr_t)src) | (COPY ? (uintptr_t)dst : 0)) & 15u) == 0;
-  // A read-only pass runs 2-3 % faster with four of these workgroups resident per CU than with the
-  // eight that fit (6.33 -> 6.50 TB/s measured in one process); the copying form wants all eight.
-  const uint32_t lds_pad = COPY ? 0u : ew::occupancy_pad(k.verify_wgs_per_cu, 4 * sizeof(uint64_t) * (kThreads / 64));
+  // A read-only pass runs faster with fewer of these workgroups resident per CU than the eight that fit
+  // (four for small buffers: 6.33 -> 6.50 TB/s measured in one process; two for large ones); the copying
+  // form wants all eight.
+  const int64_t resident = large ? k.verify_large_wgs_per_cu : k.verify_wgs_per_cu;
+  const uint32_t lds_pad = COPY ? 0u : ew::occupancy_pad(resident, 4 * sizeof(uint64_t) * (kThreads / 64));
   if (aligned)
     hipLaunchKernelGGL((ew_cksum_kernel<COPY, true>), dim3((uint32_t)grid), dim3(kThreads), lds_pad, stream,
                        (const char *)src, (char *)dst, nbytes, out, sub, accumulate);
@@ -293,7 +297,9 @@ template <bool COPY>
 int launch_cksum(const void *src, void *dst, uint64_t nbytes, ew_cksum_t *out, hipStream_t stream) {
   const bool aligned = ((((uintptr_t)src) | (COPY ? (uintptr_t)dst : 0)) & 15u) == 0;
   // Read-only passes (verify) keep the streaming kernel: with no stores for the fold to hide behind,
-  // one slot per KiB is the slower shape for them.
+  // one slot per 4 KiB is the slower shape for them (4.4 TB/s), and a read-only slot kernel with 2, 4 or 8
+  // vectors in flight per lane (one slot per 8-32 KiB) reaches 6.31-6.39 TB/s per call where the streaming
+  // kernel in its shape for large buffers gives 6.47.
   const int64_t knob = ew::knobs().cksum_mode;
   const int64_t mode = knob >= 0 ? knob : (COPY ? 0 : 1);
   if (!aligned || mode != 0) return launch_cksum_streaming<COPY>(src, dst, nbytes, out, stream);

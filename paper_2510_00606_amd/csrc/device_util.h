@@ -10,7 +10,10 @@ namespace ew {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;  // four waves of 64; at one 128-bit vector per lane a workgroup moves 4 KiB
-constexpr int kUnroll = 4;     // 128-bit loads in flight per lane where a workgroup moves more than that
+#ifndef EW_UNROLL
+#define EW_UNROLL 4
+#endif
+constexpr int kUnroll = EW_UNROLL;  // 128-bit loads in flight per lane where a workgroup moves more than that
 
 // Every byte here is touched exactly once per kernel, so loads and stores carry the nontemporal
 // hint and do not displace the tile tables from the caches.

@@ -46,6 +46,13 @@ struct Knobs {
   Knob fold_tiles_per_lane{0};  // fused unpack + snapshot: tiles per lane of the fold kernel (0 = default)
   Knob fused_mode{0};           // fused unpack + snapshot: 0 = slot per tile + fold kernel, 1 = scratch-free (atomics)
   Knob verify_wgs_per_cu{4};    // read-only streaming checksum (256 lanes; 8 fit)
+  // Read-only passes over large buffers run faster as fewer, longer streams: from verify_large_min_bytes on
+  // they use sub-blocks of verify_large_sub_bytes and verify_large_wgs_per_cu workgroups per CU instead of
+  // cksum_sub_bytes and verify_wgs_per_cu (7B rank shard, per call: 6.16-6.34 -> 6.46-6.53 TB/s; below
+  // 128 MiB the small shape is equal or better: -3 % at 32-64 MiB, -10 % at 8-16 MiB with the large one)
+  Knob verify_large_min_bytes{(int64_t)128 << 20};
+  Knob verify_large_sub_bytes{262144};
+  Knob verify_large_wgs_per_cu{2};
   Knob adam_xcd_group{256};     // optimizer step: consecutive workgroups (256 elements each) per XCD; 1 = one by one
   Knob adam_wgs_per_cu{12};     // optimizer step (one wave per workgroup; 32 fit)
 };

@@ -322,6 +322,15 @@ int ew_set_param(const char *name, int64_t value) {
   } else if (!std::strcmp(name, "verify_wgs_per_cu")) {
     if (value < 0 || value > 8) return EW_EINVAL;
     k.verify_wgs_per_cu = value;
+  } else if (!std::strcmp(name, "verify_large_min_bytes")) {
+    if (value < 0) return EW_EINVAL;
+    k.verify_large_min_bytes = value;
+  } else if (!std::strcmp(name, "verify_large_sub_bytes")) {
+    if (value < 4096 || value > (int64_t)EW_CKSUM_BLOCK || (value & (value - 1))) return EW_EINVAL;
+    k.verify_large_sub_bytes = value;
+  } else if (!std::strcmp(name, "verify_large_wgs_per_cu")) {
+    if (value < 0 || value > 8) return EW_EINVAL;
+    k.verify_large_wgs_per_cu = value;
   } else if (!std::strcmp(name, "adam_wgs_per_cu")) {
     if (value < 0 || value > 32) return EW_EINVAL;
     k.adam_wgs_per_cu = value;
@@ -354,6 +363,9 @@ int64_t ew_get_param(const char *name) {
   if (!std::strcmp(name, "fold_tiles_per_lane")) return k.fold_tiles_per_lane;
   if (!std::strcmp(name, "fused_mode")) return k.fused_mode;
   if (!std::strcmp(name, "verify_wgs_per_cu")) return k.verify_wgs_per_cu;
+  if (!std::strcmp(name, "verify_large_min_bytes")) return k.verify_large_min_bytes;
+  if (!std::strcmp(name, "verify_large_sub_bytes")) return k.verify_large_sub_bytes;
+  if (!std::strcmp(name, "verify_large_wgs_per_cu")) return k.verify_large_wgs_per_cu;
   if (!std::strcmp(name, "adam_wgs_per_cu")) return k.adam_wgs_per_cu;
   if (!std::strcmp(name, "scratch_max_concurrent")) return ew::scratch_max_concurrent(false);
   return -1;

@@ -19,7 +19,8 @@ def default_params():
     saved = {k: ew.ew_get_param(k) for k in ("tile_bytes", "tile_elems", "tile_align_bytes", "cksum_sub_bytes", "cksum_wgs_per_cu",
                                               "cksum_mode", "fused_wgs_per_cu", "fused_mode", "verify_wgs_per_cu",
                                               "snapshot_wave_min_bytes", "xcd_group_kib", "snapshot_xcd_group_kib",
-                                              "fold_tiles_per_lane")}
+                                              "fold_tiles_per_lane", "verify_large_min_bytes", "verify_large_sub_bytes",
+                                              "verify_large_wgs_per_cu")}
     yield
     for k, v in saved.items():
         ew.ew_set_param(k, v)
@@ -155,6 +156,20 @@ def test_verify_with_occupancy_caps(wgs):
     o, bit = int(rng.integers(0, nbytes)), int(rng.integers(0, 8))
     bad, diffs = verify_case(nbytes, [(o, bit)], rng)
     assert bad.tolist() == [o >> 20] and int(diffs[0, 1]) == 1 << (8 * (o % 8) + bit)
+
+
+@pytest.mark.parametrize("sub,wgs", [(262144, 2), (4096, 0), (1 << 20, 1), (65536, 8)])
+def test_verify_with_the_launch_shape_for_large_buffers(sub, wgs):
+    """The shape that large read-only passes take (fewer, longer streams), forced on small and ragged
+    buffers: it changes the launch only, never the result."""
+    ew.ew_set_param("verify_large_min_bytes", 0)
+    ew.ew_set_param("verify_large_sub_bytes", sub)
+    ew.ew_set_param("verify_large_wgs_per_cu", wgs)
+    rng = np.random.default_rng(120 + wgs)
+    for nbytes in (1, 4097, MIB - 8, 9 * MIB + 100000 + 3, 40 * MIB + 24):
+        o, bit = int(rng.integers(0, nbytes)), int(rng.integers(0, 8))
+        bad, diffs = verify_case(nbytes, [(o, bit)], rng)
+        assert bad.tolist() == [o >> 20] and int(diffs[0, 1]) == 1 << (8 * (o % 8) + bit)
 
 
 def test_verify_many_flips_ordered_and_capped():
