@@ -344,7 +344,7 @@ int ew_memcpy(const void *src, void *dst, uint64_t nbytes, void *stream);
  * (ew_snapshot uses one-wave workgroups from this size on, 256-lane ones below; default: never),
  * "snapshot_xcd_group_kib" (ew_snapshot's chunks go to the XCDs in runs of this many KiB; default 128),
  * "fused_wgs_per_cu", "verify_wgs_per_cu", "adam_wgs_per_cu" (workgroups resident per CU for the
- * kernels of ew_unpack_snapshot, ew_verify and ew_adam_step; 0 = all that fit; defaults 0, 4, 12),
+ * kernels of ew_unpack_snapshot, ew_verify and ew_adam_step; 0 = all that fit; defaults 0, 4, 10),
  * "verify_large_min_bytes", "verify_large_sub_bytes", "verify_large_wgs_per_cu" (from the first size on,
  * ew_verify reads in sub-blocks of the second size with the third number of workgroups per CU instead
  * of "cksum_sub_bytes" and "verify_wgs_per_cu": fewer, longer streams; defaults 128 MiB, 256 KiB, 2),

@@ -203,10 +203,12 @@ int ew_adam_step(void *p_bf16, float *w, float *m, float *v, const void *grad, u
   if (grid > 0x7fffffffull) return EW_EINVAL;
   uint16_t *p = (uint16_t *)p_bf16;
   hipStream_t s = (hipStream_t)stream;
-  // Eight HBM streams per wave (four read, four written): with 11-12 one-wave workgroups resident per CU
+  // Eight HBM streams per wave (four read, four written): with 10-12 one-wave workgroups resident per CU
   // the step runs 7 % faster than with the 32 that fit (6.05 -> 6.52 TB/s measured in one process;
-  // 16: 6.34, 12: 6.48, 8: 6.03).  Runs of 256 consecutive workgroups per XCD add 1-1.5 % (6.44 -> 6.53
-  // TB/s at 12 per CU; runs of 16: 5.8-5.9, runs of 4096: 6.2).
+  // 16: 5.6-6.3, 8: 6.0-6.2).  In one process on one set of buffers, eight timings each: 10 per CU
+  // 6.44-6.49 TB/s, 12 per CU 6.18-6.47 (it wanders from one timing to the next), 14: 6.38-6.46.  Runs of
+  // 256 consecutive workgroups per XCD add 1-1.5 % over one by one; runs of 64: 6.07-6.09, of 128: 6.26-6.44,
+  // of 512 and more: 6.08-6.21.
   const uint32_t lds_pad = ew::occupancy_pad(ew::knobs().adam_wgs_per_cu, 0);
   const dim3 g((uint32_t)grid), b(kThreads);
   const ew::XcdMap xg = ew::make_xcd_map((uint32_t)ew::knobs().adam_xcd_group, (uint32_t)grid);  // in workgroups (256 elements each)

@@ -54,7 +54,7 @@ struct Knobs {
   Knob verify_large_sub_bytes{262144};
   Knob verify_large_wgs_per_cu{2};
   Knob adam_xcd_group{256};     // optimizer step: consecutive workgroups (256 elements each) per XCD; 1 = one by one
-  Knob adam_wgs_per_cu{12};     // optimizer step (one wave per workgroup; 32 fit)
+  Knob adam_wgs_per_cu{10};     // optimizer step (one wave per workgroup; 32 fit)
 };
 Knobs &knobs();
 
