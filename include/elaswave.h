@@ -346,8 +346,9 @@ int ew_memcpy(const void *src, void *dst, uint64_t nbytes, void *stream);
  * "fused_wgs_per_cu", "verify_wgs_per_cu", "adam_wgs_per_cu" (workgroups resident per CU for the
  * kernels of ew_unpack_snapshot, ew_verify and ew_adam_step; 0 = all that fit; defaults 0, 4, 10),
  * "verify_large_min_bytes", "verify_large_sub_bytes", "verify_large_wgs_per_cu" (from the first size on,
- * ew_verify reads in sub-blocks of the second size with the third number of workgroups per CU instead
- * of "cksum_sub_bytes" and "verify_wgs_per_cu": fewer, longer streams; defaults 128 MiB, 256 KiB, 2),
+ * ew_verify reads in sub-blocks of up to the second size -- halved, down to 128 KiB, until every resident
+ * workgroup gets five -- with the third number of workgroups per CU, instead of "cksum_sub_bytes" and
+ * "verify_wgs_per_cu": fewer, longer streams; defaults 256 MiB, 512 KiB, 2),
  * "adam_xcd_group" (ew_adam_step's 256-element workgroups go to the XCDs in runs of this many; default 256),
  * "xcd_group_kib" (the tile kernels hand each of the 8 XCDs runs of consecutive tiles of this many
  * KiB instead of dealing tiles out one by one; 0 = one by one; default 2048),

@@ -232,7 +232,15 @@ int launch_cksum_streaming(const void *src, void *dst, uint64_t nbytes, ew_cksum
   const ew::Knobs &k = ew::knobs();
   // A read-only pass over a large buffer runs as fewer, longer streams (see Knobs::verify_large_*).
   const bool large = !COPY && nbytes >= (uint64_t)k.verify_large_min_bytes;
-  const uint32_t sub = (uint32_t)(large ? k.verify_large_sub_bytes : k.cksum_sub_bytes);
+  const int64_t resident = large ? k.verify_large_wgs_per_cu : k.verify_wgs_per_cu;
+  uint32_t sub = (uint32_t)(large ? k.verify_large_sub_bytes : k.cksum_sub_bytes);
+  if (large && resident > 0) {
+    // the largest sub-block, down to 128 KiB, that still gives every resident workgroup five sub-blocks:
+    // with three rounds or fewer the last, partly filled round shows (0.875 GB: 6.54 TB/s at 256 KiB, 6.16 at
+    // 512 KiB; 0.44 GB: 6.03 at 128 KiB, 5.78 at 256 KiB)
+    const uint64_t want = 5ull * (uint64_t)resident * (uint64_t)ew::num_cus();
+    while (sub > 131072u && nbytes / sub < want) sub >>= 1;
+  }
   const uint64_t nblocks = (nbytes + EW_CKSUM_BLOCK - 1) / EW_CKSUM_BLOCK;
   const uint32_t accumulate = sub < EW_CKSUM_BLOCK ? 1u : 0u;
   if (accumulate) {
@@ -249,7 +257,6 @@ int launch_cksum_streaming(const void *src, void *dst, uint64_t nbytes, ew_cksum
   // A read-only pass runs faster with fewer of these workgroups resident per CU than the eight that fit
   // (four for small buffers: 6.33 -> 6.50 TB/s measured in one process; two for large ones); the copying
   // form wants all eight.
-  const int64_t resident = large ? k.verify_large_wgs_per_cu : k.verify_wgs_per_cu;
   const uint32_t lds_pad = COPY ? 0u : ew::occupancy_pad(resident, 4 * sizeof(uint64_t) * (kThreads / 64));
   if (aligned)
     hipLaunchKernelGGL((ew_cksum_kernel<COPY, true>), dim3((uint32_t)grid), dim3(kThreads), lds_pad, stream,

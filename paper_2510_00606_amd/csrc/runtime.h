@@ -47,11 +47,12 @@ struct Knobs {
   Knob fused_mode{0};           // fused unpack + snapshot: 0 = slot per tile + fold kernel, 1 = scratch-free (atomics)
   Knob verify_wgs_per_cu{4};    // read-only streaming checksum (256 lanes; 8 fit)
   // Read-only passes over large buffers run faster as fewer, longer streams: from verify_large_min_bytes on
-  // they use sub-blocks of verify_large_sub_bytes and verify_large_wgs_per_cu workgroups per CU instead of
-  // cksum_sub_bytes and verify_wgs_per_cu (7B rank shard, per call: 6.16-6.34 -> 6.46-6.53 TB/s; below
-  // 128 MiB the small shape is equal or better: -3 % at 32-64 MiB, -10 % at 8-16 MiB with the large one)
-  Knob verify_large_min_bytes{(int64_t)128 << 20};
-  Knob verify_large_sub_bytes{262144};
+  // they use verify_large_wgs_per_cu workgroups per CU and sub-blocks of up to verify_large_sub_bytes (halved,
+  // down to 128 KiB, until every resident workgroup gets five of them) instead of verify_wgs_per_cu and
+  // cksum_sub_bytes.  Per call on arrays of 0.44 / 0.875 / 1.75 GB: 5.94 / 6.35 / 6.57 TB/s in the small shape,
+  // 6.03 / 6.54 / 6.81 in the large one; at 0.22 GB and below the small shape is equal or better.
+  Knob verify_large_min_bytes{(int64_t)256 << 20};
+  Knob verify_large_sub_bytes{524288};
   Knob verify_large_wgs_per_cu{2};
   Knob adam_xcd_group{256};     // optimizer step: consecutive workgroups (256 elements each) per XCD; 1 = one by one
   Knob adam_wgs_per_cu{10};     // optimizer step (one wave per workgroup; 32 fit)
