@@ -353,6 +353,8 @@ int ew_memcpy(const void *src, void *dst, uint64_t nbytes, void *stream);
  * "xcd_group_kib" (the tile kernels hand each of the 8 XCDs runs of consecutive tiles of this many
  * KiB instead of dealing tiles out one by one; 0 = one by one; default 2048),
  * "fused_mode" (0 = default; 1 forces the scratch-free form of ew_unpack_snapshot),
+ * "fused_pass_tiles" (ew_unpack_snapshot cuts its tile kernel into launches of at most this many tiles;
+ * 0 = one launch per scratch region; default 262144),
  * "fold_tiles_per_lane" (tiles each lane of ew_unpack_snapshot's fold kernel walks; 0 = default, 2),
  * "scratch_max_concurrent" (read-only statistic: the most calls that ever held a scratch region at
  * the same time; setting it to 0 resets it).

@@ -105,6 +105,8 @@ void release_tables(ew_plan_t *plan) {
 
 int launch_segcopy(const ew::TileTable &tt, const CopyTabs &tabs, uint32_t elem_size, hipStream_t stream) {
   if (tt.ntiles == 0) return EW_OK;
+  // One launch for the whole table (cutting it into launches of 64 Ki-512 Ki tiles, which gains the fused
+  // unpack + snapshot kernel 0.7-0.9 %, changes nothing here down to 256 Ki tiles and costs 0.4-3 % below).
   const uint32_t grid = (uint32_t)tt.ntiles;  // ew_plan_upload refuses tables above 2^31-1 tiles
   const ew::XcdMap g = ew::make_xcd_map(ew::xcd_group_for((uint64_t)tt.tile_bytes), grid);
   if (elem_size == 2)

@@ -44,6 +44,8 @@ struct Knobs {
   Knob fused_wgs_per_cu{0};     // fused unpack + snapshot (256 lanes; 8 fit): no cap since tiles go to XCDs in
                                 // runs (with the identity mapping six per CU were 1-5 % faster than eight)
   Knob fold_tiles_per_lane{0};  // fused unpack + snapshot: tiles per lane of the fold kernel (0 = default)
+  Knob fused_pass_tiles{262144};  // fused unpack + snapshot: at most this many tiles per launch of the tile kernel
+                                  // (0 = what the scratch region holds); the fold follows once per region
   Knob fused_mode{0};           // fused unpack + snapshot: 0 = slot per tile + fold kernel, 1 = scratch-free (atomics)
   Knob verify_wgs_per_cu{4};    // read-only streaming checksum (256 lanes; 8 fit)
   // Read-only passes over large buffers run faster as fewer, longer streams: from verify_large_min_bytes on

@@ -316,6 +316,9 @@ int ew_set_param(const char *name, int64_t value) {
   } else if (!std::strcmp(name, "fold_tiles_per_lane")) {
     if (value < 0 || value > 1024) return EW_EINVAL;
     k.fold_tiles_per_lane = value;
+  } else if (!std::strcmp(name, "fused_pass_tiles")) {
+    if (value < 0 || value > 0x7fffffff) return EW_EINVAL;
+    k.fused_pass_tiles = value;
   } else if (!std::strcmp(name, "fused_mode")) {
     if (value < 0 || value > 1) return EW_EINVAL;
     k.fused_mode = value;
@@ -361,6 +364,7 @@ int64_t ew_get_param(const char *name) {
   if (!std::strcmp(name, "adam_xcd_group")) return k.adam_xcd_group;
   if (!std::strcmp(name, "snapshot_xcd_group_kib")) return k.snapshot_xcd_group_kib;
   if (!std::strcmp(name, "fold_tiles_per_lane")) return k.fold_tiles_per_lane;
+  if (!std::strcmp(name, "fused_pass_tiles")) return k.fused_pass_tiles;
   if (!std::strcmp(name, "fused_mode")) return k.fused_mode;
   if (!std::strcmp(name, "verify_wgs_per_cu")) return k.verify_wgs_per_cu;
   if (!std::strcmp(name, "verify_large_min_bytes")) return k.verify_large_min_bytes;

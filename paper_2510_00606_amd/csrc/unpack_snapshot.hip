@@ -192,9 +192,15 @@ __global__ __launch_bounds__(kThreads) void ew_zero_records_kernel(SnapTabs st) 
   if (i < 2ull * st.nblk[k]) reinterpret_cast<uint64_t *>(st.rec[k])[i] = 0;
 }
 
+// One pass = the tiles [t0, t0 + n) whose slots fit the scratch region: the tile kernel in launches of at most
+// `per_launch` tiles, then one fold over the whole pass.  Cutting the tile kernel's work into launches of
+// about 1 GiB of destination (256 Ki tiles of 4 KiB, half a millisecond each) makes this kernel 0.7-0.9 %
+// faster than one launch of 3 ms (7B stage, one process, same buffers: 128 Ki +0.7 %, 256 Ki +0.7-0.9 %,
+// 512 Ki +0.4 %, 1 Mi +0.15 %, 64 Ki -0.2 %, 32 Ki -2.1 %), although every cut drains the GPU; the two-stream
+// kernels gain nothing from it.  Knob fused_pass_tiles.
 template <int ES>
-int launch_pass(const ew::TileTable &tt, uint64_t t0, uint64_t n, const CopyTabs &tabs, const SnapTabs &st,
-                ew_cksum_t *slots, hipStream_t stream) {
+int launch_pass(const ew::TileTable &tt, uint64_t t0, uint64_t n, uint64_t per_launch, const CopyTabs &tabs,
+                const SnapTabs &st, ew_cksum_t *slots, hipStream_t stream) {
   // Tiles per lane of the fold (knob fold_tiles_per_lane overrides).  With the lanes' open runs combined
   // across the wave before anything is added to a record, few tiles per lane are best: 1 / 2 / 4 / 8 / 16 / 32
   // per lane take 16.6 / 15.8 / 17.4 / 24.6 / 30.1 / 40.6 us on a pass of 1.76 M tiles and 3.6 / 3.8 / 4.9 /
@@ -208,16 +214,19 @@ int launch_pass(const ew::TileTable &tt, uint64_t t0, uint64_t n, const CopyTabs
   // (three HBM streams per workgroup); with runs of tiles per XCD (xcd_remap) all eight are best
   // (7b stage, fp32: 5.97 / 5.98 / 5.85 / 5.62 TB/s at 8 / 7 / 6 / 5 per CU), so no cap by default.
   const uint32_t lds_pad = ew::occupancy_pad(ew::knobs().fused_wgs_per_cu, 8 * sizeof(uint64_t) * (kThreads / 64));
-  const ew::XcdMap xcd = ew::make_xcd_map(ew::xcd_group_for((uint64_t)tt.tile_bytes), (uint32_t)n);
-  if (!slots) {  // no scratch region: the workgroups add to the records themselves
-    hipLaunchKernelGGL((ew_unpack_snap_kernel<ES, false>), dim3((uint32_t)n), dim3(kThreads), lds_pad, stream, tt.dev,
-                       t0, tabs, st, slots, xcd);
+  const uint32_t group = ew::xcd_group_for((uint64_t)tt.tile_bytes);
+  for (uint64_t off = 0; off < n; off += per_launch) {
+    const uint32_t m = (uint32_t)(n - off < per_launch ? n - off : per_launch);
+    const ew::XcdMap xcd = ew::make_xcd_map(group, m);
+    if (slots)
+      hipLaunchKernelGGL((ew_unpack_snap_kernel<ES, true>), dim3(m), dim3(kThreads), lds_pad, stream, tt.dev, t0 + off,
+                         tabs, st, slots + off, xcd);
+    else  // no scratch region: the workgroups add to the records themselves
+      hipLaunchKernelGGL((ew_unpack_snap_kernel<ES, false>), dim3(m), dim3(kThreads), lds_pad, stream, tt.dev,
+                         t0 + off, tabs, st, slots, xcd);
     EW_HIP(hipGetLastError());
-    return EW_OK;
   }
-  hipLaunchKernelGGL((ew_unpack_snap_kernel<ES, true>), dim3((uint32_t)n), dim3(kThreads), lds_pad, stream, tt.dev, t0,
-                     tabs, st, slots, xcd);
-  EW_HIP(hipGetLastError());
+  if (!slots) return EW_OK;
   hipLaunchKernelGGL(ew_fold_tiles_kernel<ES>, dim3((uint32_t)fold_grid), dim3(kThreads), 0, stream, tt.dev, t0, n,
                      kTilesPerLane, st, slots);
   EW_HIP(hipGetLastError());
@@ -261,10 +270,12 @@ int unpack_snapshot(const ew_plan_t *plan, int which, const void *stage, const v
                      dim3(kThreads), 0, stream, st);
   EW_HIP(hipGetLastError());
   const uint64_t per_pass = slots ? ew::kRegionSlots : 0x7fffffffull;
+  uint64_t per_launch = per_pass;
+  if (const int64_t cap = ew::knobs().fused_pass_tiles; cap > 0 && (uint64_t)cap < per_launch) per_launch = (uint64_t)cap;
   for (uint64_t t0 = 0; t0 < tt.ntiles; t0 += per_pass) {
     const uint64_t n = tt.ntiles - t0 < per_pass ? tt.ntiles - t0 : per_pass;
-    const int prc = elem_size == 2 ? launch_pass<2>(tt, t0, n, tabs, st, slots, stream)
-                                   : launch_pass<4>(tt, t0, n, tabs, st, slots, stream);
+    const int prc = elem_size == 2 ? launch_pass<2>(tt, t0, n, per_launch, tabs, st, slots, stream)
+                                   : launch_pass<4>(tt, t0, n, per_launch, tabs, st, slots, stream);
     if (prc != EW_OK) return prc;
   }
   return EW_OK;

@@ -19,7 +19,7 @@ def default_params():
     saved = {k: ew.ew_get_param(k) for k in ("tile_bytes", "tile_elems", "tile_align_bytes", "cksum_sub_bytes", "cksum_wgs_per_cu",
                                               "cksum_mode", "fused_wgs_per_cu", "fused_mode", "verify_wgs_per_cu",
                                               "snapshot_wave_min_bytes", "xcd_group_kib", "snapshot_xcd_group_kib",
-                                              "fold_tiles_per_lane", "verify_large_min_bytes", "verify_large_sub_bytes",
+                                              "fold_tiles_per_lane", "fused_pass_tiles", "verify_large_min_bytes", "verify_large_sub_bytes",
                                               "verify_large_wgs_per_cu")}
     yield
     for k, v in saved.items():
@@ -381,6 +381,19 @@ def test_fused_fold_with_any_number_of_tiles_per_lane(per_lane):
         reshard_case(8, 7, 0xFF & ~(1 << 5), 3_000_000 + 8 * 37, 262144, es, rng)
         reshard_case(3, 2, 0b111, 2_600_000, 99_992, es, rng)
         reshard_case(2, 3, 0b10, 1_900_003, 70_001, es, rng)
+
+
+@pytest.mark.parametrize("per_launch", [0, 1, 7, 100, 4096])
+def test_fused_unpack_in_several_launches(per_launch):
+    """The fused kernel's tiles go out in launches of a bounded size with one fold at the end: any bound,
+    also one that leaves a ragged last launch or exceeds the table, gives the oracle's bits, with and
+    without a scratch region."""
+    ew.ew_set_param("fused_pass_tiles", per_launch)
+    for mode in (0, 1):
+        ew.ew_set_param("fused_mode", mode)
+        rng = np.random.default_rng(900 + per_launch + mode)
+        reshard_case(5, 4, 0b10111, 3 * 4096 * 40 + 8 * 11, 4096, 4, rng)
+        reshard_case(4, 6, 0b1111, 250_000 * 8, 50_000 * 8, 2, rng, tile_elems=256)
 
 
 def test_fused_unpack_scratch_free_form():
