@@ -59,7 +59,7 @@ def parse():
     ap.add_argument("--no-other-path", action="store_true", help="do not time the path that is not the headline")
     ap.add_argument("--no-migration", action="store_true", help="skip the layer-migration comparison (Sec. 6.3)")
     ap.add_argument("--no-placement-trial", action="store_true",
-                    help="keep the first allocation of the new shards' snapshot copies instead of the best of a few")
+                    help="keep the plain allocation of the new shards and their snapshot copies instead of the best of a few")
     ap.add_argument("--no-workloads", action="store_true",
                     help="skip the brief measurements of the other named workloads after the timed region")
     ap.add_argument("--no-grad-snapshot", action="store_true",
@@ -169,14 +169,15 @@ def measure(args, ew, synth, torch, w, starts, A, keep_state, steps=None, warmup
     # ---------------- placement trial (set-up, untimed).  The fused kernel streams from three places at once
     # (sources, new shards, their snapshot copies), and its rate depends on which of the HBM's three 96-GiB
     # regions each of them lies in (6.2 TB/s with all three in one region, 6.3-6.4 with both written buffers in
-    # one, 6.55-6.65 otherwise).  A program sees no physical addresses, so the long-lived copies are placed the
-    # way a long-running job can place them: a few candidate allocations, one fused call on each, keep the best.
+    # one, 6.55-6.65 otherwise).  A program sees no physical addresses, so these long-lived buffers are placed
+    # the way a long-running job can place them: a few candidate allocations, one fused call on each, keep the
+    # best -- first for the snapshot copies, then for the new shards.
     placement = None
     set_bytes = sum(n * es[a] for a in A for n in new_len)
     if extras and not args.no_placement_trial and set_bytes >= (1 << 30):
         free_b, _ = torch.cuda.mem_get_info()
-        n_extra = max(0, min(3, int((free_b - (12 << 30)) // set_bytes)))
-        cands = [nsnap] + [{a: [torch.empty_like(t) for t in new[a]] for a in A} for _ in range(n_extra)]
+        n_extra = max(0, min(6, int((free_b - (16 << 30)) // set_bytes)))
+        sets = [new, nsnap] + [{a: [torch.empty_like(t) for t in new[a]] for a in A} for _ in range(n_extra)]
         tp = ew.ew_plan_bounds(w.old_dp, w.new_dp, w.alive_mask, starts)
         ew.ew_plan_upload(tp, 0, st)
         for a in A:                      # real bytes in the sources the trial reads
@@ -184,25 +185,32 @@ def measure(args, ew, synth, torch, w, starts, A, keep_state, steps=None, warmup
                 if not alive[j]:
                     ew.ew_snapshot(old[a][j], snap[a][j], old_len[j] * es[a], sums[a][j], st)
             ew.ew_pack(tp, old_after[a], snap_used[a], stage[a], es[a], st)
-        rates = []
-        for c in cands:
+
+        def fused_rate(shards, copies):
             ts = []
             for rep in range(4):
                 p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 p0.record()
                 for a in A:
-                    ew.ew_unpack_snapshot(tp, stage[a], old_after[a], snap_used[a], new[a], c[a], nsums[a], es[a], st)
+                    ew.ew_unpack_snapshot(tp, stage[a], old_after[a], snap_used[a], shards[a], copies[a], nsums[a], es[a], st)
                 p1.record()
                 torch.cuda.synchronize()
                 ts.append(p0.elapsed_time(p1))
-            rates.append(round(3 * set_bytes / sorted(ts[1:])[1] / 1e6, 1))
+            return round(3 * set_bytes / sorted(ts[1:])[1] / 1e6, 1)
+
+        # set 0 = the new shards as allocated, set 1 = their copies as allocated, sets 2.. = what came after
+        copies_rates = {i: fused_rate(sets[0], sets[i]) for i in range(1, len(sets))}
+        ci = max(copies_rates, key=copies_rates.get)
+        shards_rates = {i: (copies_rates[ci] if i == 0 else fused_rate(sets[i], sets[ci]))
+                        for i in range(len(sets)) if i != ci}
+        si = max(shards_rates, key=shards_rates.get)
         tp.close()
-        best = max(range(len(cands)), key=lambda i: rates[i])
-        nsnap = cands[best]
-        del cands, c
+        new, nsnap = sets[si], sets[ci]
+        del sets
         torch.cuda.empty_cache()
-        placement = {"fused_GBps_by_candidate": rates, "chosen": best}
-        log(f"placement trial: fused {rates} GB/s, candidate {best} kept")
+        placement = {"fused_GBps_by_copies_set": copies_rates, "copies_set": ci,
+                     "fused_GBps_by_shards_set": shards_rates, "shards_set": si}
+        log(f"placement trial: copies {copies_rates} -> set {ci}; shards {shards_rates} -> set {si}")
 
     numel = w.numel
     n_remote = stage_len
@@ -622,10 +630,11 @@ def main():
     }
     if res["placement"] is not None:
         out["placement_trial"] = dict(res["placement"], note=(
-            "set-up, before the timed region: the snapshot copies of the new shards are allocated up to four times, one "
-            "ew_unpack_snapshot of the four arrays is timed on each candidate (the first is the plain allocation) and the "
-            "fastest is kept: the kernel's rate depends on which 96-GiB regions of the HBM its three streams lie in, "
-            "which a program cannot see"))
+            "set-up, before the timed region: up to six more sets of new-shard-sized buffers are allocated behind the "
+            "plain allocation (set 0 = new shards, set 1 = their snapshot copies); one ew_unpack_snapshot of the four "
+            "arrays is timed with each set as the copies, the fastest is kept, then the same for the new shards; the rest "
+            "is freed.  The kernel's rate depends on which 96-GiB regions of the HBM its three streams lie in, which a "
+            "program cannot see"))
     if res["tiny_latency"] is not None:
         out["tiny_step_latency"] = res["tiny_latency"]
     if other is not None:
