@@ -177,7 +177,13 @@ def measure(args, ew, synth, torch, w, starts, A, keep_state, steps=None, warmup
     if extras and not args.no_placement_trial and set_bytes >= (1 << 30):
         free_b, _ = torch.cuda.mem_get_info()
         n_extra = max(0, min(6, int((free_b - (16 << 30)) // set_bytes)))
-        sets = [new, nsnap] + [{a: [torch.empty_like(t) for t in new[a]] for a in A} for _ in range(n_extra)]
+        sets = [new, nsnap]
+        for _ in range(n_extra):
+            try:
+                sets.append({a: [torch.empty_like(t) for t in new[a]] for a in A})
+            except torch.OutOfMemoryError:   # free memory in pieces too small: make do with the sets there are
+                torch.cuda.empty_cache()
+                break
         tp = ew.ew_plan_bounds(w.old_dp, w.new_dp, w.alive_mask, starts)
         ew.ew_plan_upload(tp, 0, st)
         for a in A:                      # real bytes in the sources the trial reads
