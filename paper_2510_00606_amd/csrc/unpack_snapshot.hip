@@ -197,7 +197,9 @@ __global__ __launch_bounds__(kThreads) void ew_zero_records_kernel(SnapTabs st) 
 // about 1 GiB of destination (256 Ki tiles of 4 KiB, half a millisecond each) makes this kernel 0.7-0.9 %
 // faster than one launch of 3 ms (7B stage, one process, same buffers: 128 Ki +0.7 %, 256 Ki +0.7-0.9 %,
 // 512 Ki +0.4 %, 1 Mi +0.15 %, 64 Ki -0.2 %, 32 Ki -2.1 %), although every cut drains the GPU; the two-stream
-// kernels gain nothing from it.  Knob fused_pass_tiles.
+// kernels gain nothing from it.  That is with the three streams in one 96-GiB region of the HBM (6.12 TB/s) or
+// the two written ones in one (6.36: +0.75 %); with the three in three regions (6.59) the cut costs 0.4 %.
+// Knob fused_pass_tiles.
 template <int ES>
 int launch_pass(const ew::TileTable &tt, uint64_t t0, uint64_t n, uint64_t per_launch, const CopyTabs &tabs,
                 const SnapTabs &st, ew_cksum_t *slots, hipStream_t stream) {
